@@ -1,0 +1,438 @@
+"""Pins for the CPU oracle: each oracle function is checked against something
+other than itself -- brute-force loops, closed forms from Sec. 3.3, a hand-worked
+permutation, torch's CPU scaled_dot_product_attention, or invariants."""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import svg_oracle as O
+from workloads import get_config, make_qkv, make_plain_qkv, sample_rows, planted_labels
+
+
+def f64(x):
+    return x.to(torch.float64).numpy()
+
+
+def brute_attention(q, k, v, mask, scale):
+    """Pure-Python definition: o_i = sum_j w_ij v_j, w_ij = e^{s_ij} / sum_j e^{s_ij}."""
+    t, D = len(q), len(q[0])
+    out = [[0.0] * D for _ in range(t)]
+    for i in range(t):
+        s = []
+        for j in range(len(k)):
+            if mask is None or mask[i][j]:
+                s.append((j, scale * sum(q[i][d] * k[j][d] for d in range(D))))
+        m = max(x for _, x in s)
+        z = sum(math.exp(x - m) for _, x in s)
+        for j, x in s:
+            w = math.exp(x - m) / z
+            for d in range(D):
+                out[i][d] += w * v[j][d]
+    return np.array(out)
+
+
+TINY = O.Geometry.from_config(get_config("tiny"))
+
+
+# ---------------------------------------------------------------- attention
+def test_masked_attention_all_ones_equals_bruteforce_dense():
+    rng = np.random.default_rng(0)
+    q, k, v = rng.normal(size=(5, 8)), rng.normal(size=(11, 8)), rng.normal(size=(11, 8))
+    ref = brute_attention(q.tolist(), k.tolist(), v.tolist(), None, 0.3)
+    ones = np.ones((5, 11), dtype=bool)
+    assert np.allclose(O.masked_attention(q, k, v, ones, 0.3), ref, atol=1e-13)
+    assert np.allclose(O.masked_attention(q, k, v, None, 0.3), ref, atol=1e-13)
+
+
+def test_masked_attention_random_mask_equals_bruteforce():
+    rng = np.random.default_rng(1)
+    q, k, v = rng.normal(size=(6, 4)), rng.normal(size=(9, 4)), rng.normal(size=(9, 4))
+    mask = rng.random((6, 9)) < 0.5
+    mask[np.arange(6), np.arange(6)] = True
+    ref = brute_attention(q.tolist(), k.tolist(), v.tolist(), mask.tolist(), 0.7)
+    assert np.allclose(O.masked_attention(q, k, v, mask, 0.7), ref, atol=1e-13)
+
+
+def test_attention_is_not_symmetric_in_q_and_k():
+    # a transposed operand (k q^T instead of q k^T) must fail this pin
+    q = np.array([[1.0, 0.0], [0.0, 0.0]])
+    k = np.array([[10.0, 0.0], [0.0, 0.0]])
+    v = np.array([[1.0, 0.0], [0.0, 1.0]])
+    o = O.masked_attention(q, k, v, None, 1.0)
+    w0 = math.exp(10.0) / (math.exp(10.0) + 1.0)
+    assert np.allclose(o, [[w0, 1 - w0], [0.5, 0.5]], atol=1e-15)
+
+
+def test_softmax_rows_sum_to_one_and_respect_mask():
+    q, k, _ = (f64(x)[0, 0] for x in make_qkv(get_config("tiny")))
+    for mask in (None, O.spatial_mask(TINY), O.temporal_mask(TINY)):
+        w = O.attention_weights(q, k, mask, TINY.scale)
+        assert np.allclose(w.sum(axis=1), 1.0, atol=1e-14)
+        assert (w >= 0).all()
+        if mask is not None:
+            assert (w[~mask] == 0).all()
+
+
+def test_masked_attention_matches_torch_sdpa_fp64():
+    q, k, v = (x.to(torch.float64)[0] for x in make_qkv(get_config("tiny")))
+    for mask in (O.spatial_mask(TINY), O.temporal_mask(TINY)):
+        ref = torch.nn.functional.scaled_dot_product_attention(
+            q, k, v, attn_mask=torch.from_numpy(mask)[None], scale=TINY.scale).numpy()
+        for h in range(4):
+            got = O.masked_attention(q[h].numpy(), k[h].numpy(), v[h].numpy(), mask, TINY.scale)
+            assert np.allclose(got, ref[h], atol=1e-12)
+
+
+def test_shift_invariance_and_single_key():
+    rng = np.random.default_rng(2)
+    q, k, v = rng.normal(size=(3, 4)), rng.normal(size=(7, 4)), rng.normal(size=(7, 4))
+    # one kept key -> output is that key's value exactly
+    mask = np.zeros((3, 7), dtype=bool)
+    mask[:, 4] = True
+    assert np.array_equal(O.masked_attention(q, k, v, mask, 1.0), np.tile(v[4], (3, 1)))
+    # identical keys -> output is the mean of the values
+    k2 = np.tile(k[0], (7, 1))
+    assert np.allclose(O.masked_attention(q, k2, v, None, 1.0), np.tile(v.mean(0), (3, 1)), atol=1e-15)
+
+
+# ---------------------------------------------------------------- masks
+def test_token_coords_prefix_and_suffix():
+    g = O.Geometry(1, 1, 2, 3, 2, 4, text_first=1)
+    is_text, fr, po = O.token_coords(g)
+    assert is_text.tolist() == [True, True] + [False] * 6
+    assert fr.tolist() == [-1, -1, 0, 0, 0, 1, 1, 1]
+    assert po.tolist() == [-1, -1, 0, 1, 2, 0, 1, 2]
+    g = O.Geometry(1, 1, 2, 3, 2, 4, text_first=0)
+    is_text, fr, po = O.token_coords(g)
+    assert is_text.tolist() == [False] * 6 + [True, True]
+    assert fr.tolist() == [0, 0, 0, 1, 1, 1, -1, -1]
+    assert po.tolist() == [0, 1, 2, 0, 1, 2, -1, -1]
+
+
+def test_masks_hand_worked_example():
+    # F=3 frames of P=2 tokens, one text token last, w_s=0, w_t=0
+    g = O.Geometry(1, 1, 3, 2, 1, 4, text_first=0, w_s=0, w_t=0)
+    s = O.spatial_mask(g).astype(int)
+    t = O.temporal_mask(g).astype(int)
+    assert s.tolist() == [
+        [1, 1, 0, 0, 0, 0, 1],
+        [1, 1, 0, 0, 0, 0, 1],
+        [0, 0, 1, 1, 0, 0, 1],
+        [0, 0, 1, 1, 0, 0, 1],
+        [0, 0, 0, 0, 1, 1, 1],
+        [0, 0, 0, 0, 1, 1, 1],
+        [1, 1, 1, 1, 1, 1, 1]]
+    assert t.tolist() == [
+        [1, 0, 1, 0, 1, 0, 1],
+        [0, 1, 0, 1, 0, 1, 1],
+        [1, 0, 1, 0, 1, 0, 1],
+        [0, 1, 0, 1, 0, 1, 1],
+        [1, 0, 1, 0, 1, 0, 1],
+        [0, 1, 0, 1, 0, 1, 1],
+        [1, 1, 1, 1, 1, 1, 1]]
+
+
+def test_sink_first_frame_keeps_frame0_keys():
+    g = O.Geometry(1, 1, 3, 2, 1, 4, text_first=0, w_s=0, w_t=0, sink_first_frame=1)
+    s = O.spatial_mask(g)
+    assert s[:, :2].all() and not s[4, 2] and not s[4, 3]
+    assert O.temporal_mask(g)[:, :2].all()
+
+
+@pytest.mark.parametrize("name", ["tiny", "mid64", "mid128"])
+def test_mask_density_closed_form_interior_rows(name):
+    """Sec. 3.3: a spatial head keeps c_s of N frames, a temporal head c_t of L
+    tokens per frame; with symmetric windows c_s = 2 w_s + 1 and c_t = 2 w_t + 1
+    for rows whose window is not clipped."""
+    g = O.Geometry.from_config(get_config(name))
+    is_text, fr, po = O.token_coords(g)
+    vid = ~is_text
+    ms, mt = O.spatial_mask(g), O.temporal_mask(g)
+    for i in range(g.N):
+        if is_text[i]:
+            assert ms[i].all() and mt[i].all()
+            continue
+        if g.w_s <= fr[i] < g.F - g.w_s:
+            assert ms[i][vid].sum() == (2 * g.w_s + 1) * g.P
+        if g.w_t <= po[i] < g.P - g.w_t:
+            assert mt[i][vid].sum() == (2 * g.w_t + 1) * g.F
+        assert ms[i][is_text].all() and mt[i][is_text].all()
+        assert ms[i, i] and mt[i, i]
+    # masks are symmetric (|a-b| windows, text in both directions)
+    assert np.array_equal(ms, ms.T) and np.array_equal(mt, mt.T)
+
+
+def test_wide_windows_give_all_ones():
+    g = O.Geometry(1, 1, 4, 6, 3, 8, w_s=3, w_t=5)
+    assert O.spatial_mask(g).all() and O.temporal_mask(g).all()
+
+
+def test_mask_rows_subset():
+    rows = sample_rows(get_config("tiny"))
+    assert np.array_equal(O.spatial_mask(TINY, rows), O.spatial_mask(TINY)[rows])
+    assert np.array_equal(O.temporal_mask(TINY, rows), O.temporal_mask(TINY)[rows])
+
+
+# ---------------------------------------------------------------- layout
+def test_layout_hand_worked_example():
+    # 1 text token first, F=2 frames of P=3 tokens: [t, a0 a1 a2, b0 b1 b2]
+    g = O.Geometry(1, 1, 2, 3, 1, 1, text_first=1)
+    x = np.array([[100.], [0.], [1.], [2.], [10.], [11.], [12.]])
+    y = O.layout_fwd(x, g)
+    assert y[:, 0].tolist() == [100., 0., 10., 1., 11., 2., 12.]
+    assert O.layout_inv(y, g)[:, 0].tolist() == x[:, 0].tolist()
+    # text last
+    g = O.Geometry(1, 1, 2, 3, 1, 1, text_first=0)
+    x = np.array([[0.], [1.], [2.], [10.], [11.], [12.], [100.]])
+    assert O.layout_fwd(x, g)[:, 0].tolist() == [0., 10., 1., 11., 2., 12., 100.]
+
+
+@pytest.mark.parametrize("name", ["tiny", "mid64", "mid128"])
+def test_layout_is_reshape_transpose_and_inverts_bit_exactly(name):
+    cfg = get_config(name)
+    g = O.Geometry.from_config(cfg)
+    rng = np.random.default_rng(3)
+    x = rng.integers(0, 2 ** 16, size=(g.B, g.H, g.N, g.D), dtype=np.uint16)
+    y = O.layout_fwd(x, g)
+    vid = slice(g.off, g.off + g.F * g.P)
+    ref = x[:, :, vid].reshape(g.B, g.H, g.F, g.P, g.D).transpose(0, 1, 3, 2, 4).reshape(g.B, g.H, -1, g.D)
+    assert np.array_equal(y[:, :, vid], ref)
+    txt = np.ones(g.N, bool)
+    txt[vid] = False
+    assert np.array_equal(y[:, :, txt], x[:, :, txt])
+    assert np.array_equal(O.layout_inv(y, g), x)
+    assert np.array_equal(O.layout_fwd(O.layout_inv(x, g), g), x)
+    perm = O.layout_perm(g)
+    assert sorted(perm.tolist()) == list(range(g.N))
+
+
+def test_layout_degenerate_single_frame_or_single_position_is_identity():
+    for F, P in ((1, 7), (7, 1)):
+        g = O.Geometry(1, 1, F, P, 2, 3)
+        assert O.layout_perm(g).tolist() == list(range(g.N))
+
+
+def test_layout_equivalence_of_attention():
+    """Sec. 4.2: permuting the tokens (and the mask with them) and permuting the
+    result back leaves the attention output unchanged."""
+    g = TINY
+    q, k, v = (f64(x)[0, 2] for x in make_qkv(get_config("tiny")))
+    perm = O.layout_perm(g)
+    inv = np.empty_like(perm)
+    inv[perm] = np.arange(g.N)
+    m = O.temporal_mask(g)
+    mp = m[inv][:, inv]
+    o_ref = O.masked_attention(q, k, v, m, g.scale)
+    o_p = O.masked_attention(O.layout_fwd(q, g), O.layout_fwd(k, g), O.layout_fwd(v, g), mp, g.scale)
+    assert np.allclose(O.layout_inv(o_p, g), o_ref, atol=1e-12)
+
+
+# ---------------------------------------------------------------- tile lists
+def closed_form_tiles(g, pattern):
+    """Independent derivation by interval arithmetic: in its own order a pattern
+    keeps, for a query tile covering groups ga..gb (frames for spatial, positions
+    for temporal), the contiguous key range of groups ga-w .. gb+w plus the text
+    range; a tile with a text query keeps everything."""
+    nq, nk = O.n_tiles(g)
+    unit, groups, w = (g.P, g.F, g.w_s) if pattern == O.SPATIAL else (g.F, g.P, g.w_t)
+    off, V = g.off, g.F * g.P
+    out = []
+    for a in range(nq):
+        r0, r1 = a * g.block_m, min(g.N, (a + 1) * g.block_m) - 1
+        has_text = r0 < off or r1 >= off + V
+        if has_text and g.T > 0:
+            out.append(list(range(nk)))
+            continue
+        ga, gb = (r0 - off) // unit, (r1 - off) // unit
+        lo = off + max(0, ga - w) * unit
+        hi = off + min(groups, gb + w + 1) * unit - 1
+        kept = set(range(lo // g.block_n, hi // g.block_n + 1))
+        if g.T > 0:
+            t0, t1 = (0, g.T - 1) if g.text_first else (V, g.N - 1)
+            kept |= set(range(t0 // g.block_n, t1 // g.block_n + 1))
+        out.append(sorted(kept))
+    return out
+
+
+@pytest.mark.parametrize("name", ["tiny", "mid64", "mid128"])
+@pytest.mark.parametrize("pattern", [O.SPATIAL, O.TEMPORAL])
+def test_tile_list_matches_closed_form_and_full_matrix_bruteforce(name, pattern):
+    g = O.Geometry.from_config(get_config(name))
+    rp, ci = O.tile_list(g, pattern)
+    nq, nk = O.n_tiles(g)
+    assert rp[0] == 0 and rp[-1] == len(ci) and len(rp) == nq + 1
+    ref = closed_form_tiles(g, pattern)
+    for a in range(nq):
+        assert ci[rp[a]:rp[a + 1]].tolist() == ref[a]
+    # brute force over the full N x N element mask in that pattern's order
+    if pattern == O.SPATIAL:
+        m = O.spatial_mask(g)
+    else:
+        perm = O.layout_perm(g)
+        inv = np.empty_like(perm)
+        inv[perm] = np.arange(g.N)
+        m = O.temporal_mask(g)[inv][:, inv]
+    for a in range(nq):
+        for b in range(nk):
+            blk = m[a * g.block_m:(a + 1) * g.block_m, b * g.block_n:(b + 1) * g.block_n]
+            assert bool(blk.any()) == (b in ci[rp[a]:rp[a + 1]])
+    # the block mask covers the element mask
+    assert (O.block_mask(g, rp, ci) | ~m).all()
+
+
+def test_tile_density_follows_sec33_for_aligned_shape():
+    """With tile-aligned frames, no text and unclipped windows the kept fraction of
+    a spatial head's tiles is exactly c_s/N_frames (Sec. 3.3)."""
+    g = O.Geometry(1, 1, 8, 128, 0, 64, w_s=1, w_t=0, block_m=128, block_n=64)
+    rp, ci = O.tile_list(g, O.SPATIAL)
+    per_row = np.diff(rp)
+    assert per_row[3] == 3 * 2 and per_row[0] == 2 * 2 and per_row[-1] == 2 * 2
+    # temporal in P-outer order: band of (2 w_t + 1) * F tokens around the diagonal
+    g = O.Geometry(1, 1, 8, 128, 0, 64, w_s=0, w_t=8, block_m=128, block_n=64)
+    rp, ci = O.tile_list(g, O.TEMPORAL)
+    a = 3   # rows 384..511 = positions 48..63 -> positions 40..71 -> tokens 320..575
+    assert ci[rp[a]:rp[a + 1]].tolist() == list(range(320 // 64, 575 // 64 + 1))
+
+
+# ---------------------------------------------------------------- block-sparse attention
+def test_sparse_attention_with_full_list_is_dense():
+    g = TINY
+    q, k, v = (f64(x)[0, 1] for x in make_qkv(get_config("tiny")))
+    rp, ci = O.full_tile_list(g)
+    dense = brute_attention(q[:40].tolist(), k.tolist(), v.tolist(), None, g.scale)
+    got = O.sparse_attention_head(q, k, v, rp, ci, g)
+    assert np.allclose(got[:40], dense, atol=1e-13)
+    assert np.allclose(got, O.dense_attention_head(q, k, v, g), atol=1e-13)
+
+
+def test_sparse_attention_equals_masked_attention_with_block_mask():
+    g = TINY
+    q, k, v = (f64(x)[0, 3] for x in make_qkv(get_config("tiny")))
+    for pattern in (O.SPATIAL, O.TEMPORAL):
+        rp, ci = O.tile_list(g, pattern)
+        assert rp[-1] < 81   # something is actually skipped
+        bm = O.block_mask(g, rp, ci)
+        ref = O.masked_attention(q, k, v, bm, g.scale)
+        assert np.allclose(O.sparse_attention_head(q, k, v, rp, ci, g), ref, atol=1e-13)
+        rows = [0, 17, 100, 271]
+        bf = brute_attention(q[rows].tolist(), k.tolist(), v.tolist(), bm[rows].tolist(), g.scale)
+        assert np.allclose(ref[rows], bf, atol=1e-13)
+
+
+def test_wide_spatial_window_makes_sparse_dense():
+    cfg = get_config("tiny", w_s=3)
+    g = O.Geometry.from_config(cfg)
+    rp, ci = O.tile_list(g, O.SPATIAL)
+    frp, fci = O.full_tile_list(g)
+    assert np.array_equal(rp, frp) and np.array_equal(ci, fci)
+
+
+def test_sparse_attention_sampled_tiles_leave_rest_nan():
+    g = TINY
+    q, k, v = (f64(x)[0, 0] for x in make_qkv(get_config("tiny")))
+    rp, ci = O.tile_list(g, O.SPATIAL)
+    full = O.sparse_attention_head(q, k, v, rp, ci, g)
+    part = O.sparse_attention_head(q, k, v, rp, ci, g, q_tiles=[2, 8])
+    assert np.array_equal(part[64:96], full[64:96]) and np.array_equal(part[256:], full[256:])
+    assert np.isnan(part[:64]).all()
+
+
+# ---------------------------------------------------------------- profiling
+def test_profile_mse_bruteforce_one_head():
+    cfg = get_config("tiny")
+    g = TINY
+    q, k, v = (f64(x) for x in make_qkv(cfg))
+    rows = sample_rows(cfg)
+    mse, labels = O.profile_heads(q, k, v, rows, g)
+    h = 2
+    ql = q[0, h][rows].tolist()
+    kl, vl = k[0, h].tolist(), v[0, h].tolist()
+    full = brute_attention(ql, kl, vl, None, g.scale)
+    sp = brute_attention(ql, kl, vl, O.spatial_mask(g)[rows].tolist(), g.scale)
+    tp = brute_attention(ql, kl, vl, O.temporal_mask(g)[rows].tolist(), g.scale)
+    ms = sum((full[i][d] - sp[i][d]) ** 2 for i in range(len(rows)) for d in range(g.D)) / (len(rows) * g.D)
+    mt = sum((full[i][d] - tp[i][d]) ** 2 for i in range(len(rows)) for d in range(g.D)) / (len(rows) * g.D)
+    assert np.isclose(mse[0, h, 0], ms, rtol=1e-10) and np.isclose(mse[0, h, 1], mt, rtol=1e-10)
+    assert labels[0, h] == (O.SPATIAL if ms < mt else O.TEMPORAL)
+
+
+def test_profile_full_window_gives_zero_error():
+    cfg = get_config("tiny", w_s=3, w_t=63)
+    g = O.Geometry.from_config(cfg)
+    q, k, v = (f64(x) for x in make_qkv(cfg))
+    mse, labels = O.profile_heads(q, k, v, sample_rows(cfg), g)
+    assert (mse == 0).all()
+    assert (labels == O.TEMPORAL).all()      # tie -> not strictly smaller -> temporal
+
+
+def test_profile_all_rows_is_oracle_identification():
+    """Sec. 3.2: with every row sampled the profile is the full comparison of the
+    two sparse outputs with dense attention."""
+    cfg = get_config("tiny")
+    g = TINY
+    q, k, v = (f64(x) for x in make_qkv(cfg))
+    mse, _ = O.profile_heads(q, k, v, np.arange(g.N), g)
+    for h in range(g.H):
+        dense = O.dense_attention_head(q[0, h], k[0, h], v[0, h], g)
+        for x, m in ((0, O.spatial_mask(g)), (1, O.temporal_mask(g))):
+            sp = O.masked_attention(q[0, h], k[0, h], v[0, h], m, g.scale)
+            assert np.isclose(mse[0, h, x], ((dense - sp) ** 2).mean(), rtol=1e-12)
+
+
+def test_profile_row_order_does_not_matter_and_text_rows_add_nothing():
+    cfg = get_config("tiny")
+    g = TINY
+    q, k, v = (f64(x) for x in make_qkv(cfg))
+    rows = sample_rows(cfg)
+    a, _ = O.profile_heads(q, k, v, rows, g)
+    b, _ = O.profile_heads(q, k, v, rows[::-1].copy(), g)
+    assert np.allclose(a, b, rtol=1e-12)
+    # text rows are dense under both masks: zero error
+    c, _ = O.profile_heads(q, k, v, np.arange(g.T), g)
+    assert (c == 0).all()
+
+
+@pytest.mark.parametrize("name", ["tiny", "mid64", "mid128"])
+def test_planted_heads_are_classified(name):
+    cfg = get_config(name)
+    g = O.Geometry.from_config(cfg)
+    q, k, v = (f64(x) for x in make_qkv(cfg))
+    mse, labels = O.profile_heads(q, k, v, sample_rows(cfg), g)
+    assert np.array_equal(labels.reshape(-1), planted_labels(cfg))
+    assert (mse >= 0).all()
+    lo, hi = mse.min(axis=-1), mse.max(axis=-1)
+    assert (hi > 10 * lo).all()              # decided by a wide margin, not a near tie
+
+
+# ---------------------------------------------------------------- whole layer
+def test_layer_equals_element_level_definition():
+    """Spatial heads: masked attention with the spatial block mask in the original
+    order.  Temporal heads: masked attention in the original order with the
+    temporal block mask pulled back through the permutation."""
+    cfg = get_config("tiny")
+    g = TINY
+    q, k, v = (f64(x) for x in make_qkv(cfg))
+    labels = planted_labels(cfg).reshape(g.B, g.H)
+    out = O.svg_attention_layer(q, k, v, labels, g)
+    perm = O.layout_perm(g)
+    bs = O.block_mask(g, *O.tile_list(g, O.SPATIAL))
+    bt = O.block_mask(g, *O.tile_list(g, O.TEMPORAL))[perm][:, perm]
+    for h in range(g.H):
+        m = bs if labels[0, h] == O.SPATIAL else bt
+        ref = O.masked_attention(q[0, h], k[0, h], v[0, h], m, g.scale)
+        assert np.allclose(out[0, h], ref, atol=1e-12)
+
+
+def test_flop_model_sec33():
+    """Sec. 3.3: dense cost 4 L^2 N^2 H; spatial keeps c_s/N of it, temporal c_t/L.
+    Counting kept elements of the masks (no text) reproduces both fractions for
+    unclipped rows."""
+    g = O.Geometry(1, 1, 9, 20, 0, 8, w_s=2, w_t=3)
+    ms, mt = O.spatial_mask(g), O.temporal_mask(g)
+    _, fr, po = O.token_coords(g)
+    inner_s = (fr >= 2) & (fr < 7)
+    inner_t = (po >= 3) & (po < 17)
+    assert np.allclose(ms[inner_s].mean(), 5 / 9)
+    assert np.allclose(mt[inner_t].mean(), 7 / 20)
