@@ -1,0 +1,157 @@
+/*
+ * svg.h -- C ABI of the MI355X (gfx950) sparse 3D attention library.
+ *
+ * The library implements the attention hot path of Sparse VideoGen
+ * (arXiv 2502.01776): per-head online profiling (Alg. 1, Sec. 4.1), the layout
+ * transformation that makes the temporal pattern block-contiguous and its
+ * inverse (Sec. 4.2, Fig. 4), a block-sparse FlashAttention-style forward pass
+ * over the kept tiles (Sec. 4.3), and a dense forward pass as the in-library
+ * baseline (the paper's baseline is dense FlashAttention, Sec. 5.3).
+ *
+ * Conventions for every entry point
+ *   - Tensors q, k, v, o are DEVICE pointers to contiguous bf16 arrays of shape
+ *     [B, H, N, D], N = F*P + T, 16-byte aligned.  A video token of frame f and
+ *     in-frame position p sits at row off + f*P + p ("F-outer" order), where
+ *     off = T if text_first else 0; the T text tokens occupy [0,T) or [F*P,N).
+ *     The transformed ("P-outer") order puts that token at row off + p*F + f.
+ *   - All pointers are owned by the caller.  The library allocates no device
+ *     memory, keeps no state between calls, and never synchronises the host:
+ *     kernels are enqueued on `stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream) and the call returns.
+ *   - Return value: SVG_OK (0) or a negative svg_status.  Arguments are checked on
+ *     the host before anything is launched; on error nothing is enqueued.
+ *   - Head labels: SVG_HEAD_SPATIAL (0) or SVG_HEAD_TEMPORAL (1), one uint8 per
+ *     (b,h), index b*H + h.  Alg. 1's boolean best_mask_config is true for spatial.
+ */
+#ifndef SVG_H_
+#define SVG_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct svg_shape {
+  int32_t B, H;             /* batch, heads                                         */
+  int32_t F, P, T;          /* frames, tokens per frame, text tokens; N = F*P + T   */
+  int32_t D;                /* head dimension: 64 or 128                            */
+  int32_t text_first;       /* 1: text rows are [0,T); 0: text rows are [F*P, N)    */
+  int32_t w_s;              /* spatial half-window, frames:   keep |f_i-f_j| <= w_s */
+  int32_t w_t;              /* temporal half-window, positions: keep |p_i-p_j| <= w_t */
+  int32_t sink_first_frame; /* 0/1: both patterns also keep the keys of frame 0 (Sec. 3.1) */
+  int32_t block_m, block_n; /* query-tile rows x key-tile columns: 128x64 or 32x32  */
+  float softmax_scale;      /* <= 0 selects 1/sqrt(D)                               */
+} svg_shape_t;
+
+enum { SVG_HEAD_SPATIAL = 0, SVG_HEAD_TEMPORAL = 1 };
+
+typedef enum svg_status {
+  SVG_OK = 0,
+  SVG_ERR_INVALID_ARG = -1, /* NULL pointer, non-positive size, misaligned tensor, bad pattern */
+  SVG_ERR_UNSUPPORTED = -2, /* D or tile size the kernels are not built for, N too large */
+  SVG_ERR_WORKSPACE = -3,   /* workspace missing or smaller than svg_workspace_bytes() */
+  SVG_ERR_ALIAS = -4,       /* in and out overlap where they must not */
+  SVG_ERR_HIP = -5          /* the HIP runtime reported a launch error */
+} svg_status;
+
+/* Text for a status code; never NULL. */
+const char* svg_strerror(int status);
+
+/* Library version, "major.minor". */
+const char* svg_version(void);
+
+/* Bytes of device workspace svg_profile_heads needs for `t` sampled rows
+ * (three fp32 outputs of shape [B,H,t,D]).  0 if shape is invalid. */
+size_t svg_workspace_bytes(const svg_shape_t* shape, int32_t t);
+
+/* Number of query tiles and key tiles: ceil(N/block_m), ceil(N/block_n). */
+int svg_tile_counts(const svg_shape_t* shape, int32_t* nq, int32_t* nk);
+
+/*
+ * Kept-tile list of one pattern (Fig. 4; Sec. 4.3 "block sparse attention").
+ * HOST function, pure in its arguments.  pattern is SVG_HEAD_SPATIAL (rows and
+ * columns in F-outer order) or SVG_HEAD_TEMPORAL (P-outer order).  Tile (a,b)
+ * covers rows [a*block_m, min(N,(a+1)*block_m)) and columns
+ * [b*block_n, min(N,(b+1)*block_n)) and is kept iff at least one (query, key)
+ * pair inside it is kept by the pattern's element mask: either token is text, or
+ * |f_i-f_j| <= w_s (spatial) / |p_i-p_j| <= w_t (temporal), or the key is in
+ * frame 0 and sink_first_frame is set (Sec. 3.1, Sec. 3.3).
+ *   row_ptr  host int32 [nq+1], written always
+ *   col_idx  host int32 [cap], ascending within a row; may be NULL for a size query
+ *   nnz_out  receives the number of kept tiles
+ * If col_idx is non-NULL and cap < nnz: SVG_ERR_INVALID_ARG, nnz_out still set.
+ */
+int svg_tile_list_build(const svg_shape_t* shape, int pattern, int32_t* row_ptr,
+                        int32_t* col_idx, int64_t cap, int64_t* nnz_out);
+
+/*
+ * Online profiling (Alg. 1; Sec. 4.1).  For every head and each of the t sampled
+ * query rows, computes attention against ALL keys three times -- unmasked, with
+ * the spatial element mask and with the temporal element mask, all in the
+ * original F-outer order -- then MSE_x = mean over (row, channel) of
+ * (O_full - O_x)^2, and label = spatial iff MSE_s < MSE_t (ties: temporal).
+ *   q, k, v   device bf16 [B,H,N,D], F-outer order
+ *   rows      device int32 [t], each in [0,N) (not checked: out-of-range rows are
+ *             undefined behaviour); one set shared by all heads
+ *   labels    device uint8 [B*H], written
+ *   mse       device float [B*H*2] = {MSE_s, MSE_t} per head, written; may be NULL
+ *   workspace device, >= svg_workspace_bytes(shape, t), 16-byte aligned
+ * Runs bf16 MFMA with fp32 accumulation and fp32 softmax; results are
+ * deterministic (no atomics).
+ */
+int svg_profile_heads(const svg_shape_t* shape, const void* q, const void* k, const void* v,
+                      const int32_t* rows, int32_t t, uint8_t* labels, float* mse,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * Layout transformation (Sec. 4.2, Fig. 4): for heads labelled temporal,
+ * out[b,h, off + p*F + f, :] = in[b,h, off + f*P + p, :]; text rows and heads
+ * labelled spatial are copied unchanged, so `out` is always fully written.
+ * labels == NULL treats every head as temporal.  in and out must not overlap
+ * (SVG_ERR_ALIAS).  Bit-exact data movement.
+ */
+int svg_layout_fwd(const svg_shape_t* shape, const void* in, void* out, const uint8_t* labels,
+                   void* stream);
+
+/* Inverse of svg_layout_fwd: out[b,h, off + f*P + p, :] = in[b,h, off + p*F + f, :]
+ * for temporal heads; everything else copied. */
+int svg_layout_inv(const svg_shape_t* shape, const void* in, void* out, const uint8_t* labels,
+                   void* stream);
+
+/*
+ * Block-sparse attention forward (Sec. 4.3).  For each head and query tile a,
+ * o[rows of a] = softmax(scale * q k^T) v over all in-range keys of the key tiles
+ * listed for a in that head's tile list; tiles not listed are never read.
+ * Head (b,h) uses the spatial list if labels[b*H+h] == SVG_HEAD_SPATIAL and the
+ * temporal list otherwise; labels == NULL uses the spatial list for all heads.
+ *   q, k, v, o  device bf16 [B,H,N,D]; temporal heads are expected in P-outer
+ *               order (svg_layout_fwd applied) and o is written in the same order
+ *               as q (apply svg_layout_inv afterwards)
+ *   row_ptr_*   device int32 [nq+1];  col_idx_*  device int32 [nnz]  (CSR from
+ *               svg_tile_list_build, uploaded by the caller; the temporal pair may
+ *               be NULL when labels == NULL).  Entries are not range-checked on
+ *               the device: a column >= nk is undefined behaviour.
+ * A query tile with an empty list yields zeros.  workspace is reserved (may be
+ * NULL, 0).
+ */
+int svg_sparse_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, const void* v,
+                        void* o, const uint8_t* labels, const int32_t* row_ptr_s,
+                        const int32_t* col_idx_s, const int32_t* row_ptr_t,
+                        const int32_t* col_idx_t, void* workspace, size_t workspace_bytes,
+                        void* stream);
+
+/*
+ * Dense attention forward, o = softmax(scale * q k^T) v per head: the baseline
+ * the paper measures against (Sec. 5.3) and the pass used on the dense warm-up
+ * steps (Sec. 5.1).  Same tensors and precision as svg_sparse_attn_fwd; every
+ * tile is computed.  workspace is reserved (may be NULL, 0).
+ */
+int svg_dense_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, const void* v,
+                       void* o, void* workspace, size_t workspace_bytes, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SVG_H_ */

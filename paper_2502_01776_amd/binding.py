@@ -1,0 +1,173 @@
+"""ctypes binding of include/svg.h: same names, argument marshalling only.
+
+Device tensors are torch tensors (used for memory and streams only); every step of
+the path runs inside the library's kernels.  There is no fallback: if the shared
+object is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libsvg_gfx950.so")
+
+SVG_HEAD_SPATIAL = 0
+SVG_HEAD_TEMPORAL = 1
+SVG_OK = 0
+
+EXPORTS = ("svg_strerror", "svg_version", "svg_workspace_bytes", "svg_tile_counts",
+           "svg_tile_list_build", "svg_profile_heads", "svg_layout_fwd", "svg_layout_inv",
+           "svg_sparse_attn_fwd", "svg_dense_attn_fwd")
+
+
+class SvgShape(C.Structure):
+    _fields_ = [("B", C.c_int32), ("H", C.c_int32), ("F", C.c_int32), ("P", C.c_int32),
+                ("T", C.c_int32), ("D", C.c_int32), ("text_first", C.c_int32),
+                ("w_s", C.c_int32), ("w_t", C.c_int32), ("sink_first_frame", C.c_int32),
+                ("block_m", C.c_int32), ("block_n", C.c_int32), ("softmax_scale", C.c_float)]
+
+    @property
+    def N(self):
+        return self.F * self.P + self.T
+
+
+class SvgError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {svg_strerror(status)} ({status})")
+
+
+_lib = None
+
+
+def lib():
+    """The loaded shared object.  Raises FileNotFoundError if it was never built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} not found: build it with `python -m paper_2502_01776_amd.build` "
+                "(there is no CPU fallback)")
+        L = C.CDLL(LIB_PATH)
+        sp = C.POINTER(SvgShape)
+        vp, i32p = C.c_void_p, C.POINTER(C.c_int32)
+        L.svg_strerror.restype = C.c_char_p
+        L.svg_strerror.argtypes = [C.c_int]
+        L.svg_version.restype = C.c_char_p
+        L.svg_version.argtypes = []
+        L.svg_workspace_bytes.restype = C.c_size_t
+        L.svg_workspace_bytes.argtypes = [sp, C.c_int32]
+        L.svg_tile_counts.restype = C.c_int
+        L.svg_tile_counts.argtypes = [sp, i32p, i32p]
+        L.svg_tile_list_build.restype = C.c_int
+        L.svg_tile_list_build.argtypes = [sp, C.c_int, vp, vp, C.c_int64, C.POINTER(C.c_int64)]
+        L.svg_profile_heads.restype = C.c_int
+        L.svg_profile_heads.argtypes = [sp, vp, vp, vp, vp, C.c_int32, vp, vp, vp, C.c_size_t, vp]
+        for name in ("svg_layout_fwd", "svg_layout_inv"):
+            f = getattr(L, name)
+            f.restype = C.c_int
+            f.argtypes = [sp, vp, vp, vp, vp]
+        L.svg_sparse_attn_fwd.restype = C.c_int
+        L.svg_sparse_attn_fwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.svg_dense_attn_fwd.restype = C.c_int
+        L.svg_dense_attn_fwd.argtypes = [sp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        _lib = L
+    return _lib
+
+
+def shape_from_config(cfg: dict, **overrides) -> SvgShape:
+    keys = ("B", "H", "F", "P", "T", "D", "text_first", "w_s", "w_t", "sink_first_frame",
+            "block_m", "block_n")
+    vals = {k: int(cfg[k]) for k in keys}
+    vals.update(overrides)
+    return SvgShape(softmax_scale=float(cfg.get("softmax_scale", 0.0)), **vals)
+
+
+def _check(status, where):
+    if status != SVG_OK:
+        raise SvgError(status, where)
+
+
+def _ptr(x):
+    """Device (or host) address of a torch tensor / numpy array / int / None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if isinstance(x, np.ndarray):
+        return x.ctypes.data
+    return x.data_ptr()
+
+
+def _stream(stream):
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+def svg_strerror(status: int) -> str:
+    return lib().svg_strerror(int(status)).decode()
+
+
+def svg_version() -> str:
+    return lib().svg_version().decode()
+
+
+def svg_workspace_bytes(shape: SvgShape, t: int) -> int:
+    return int(lib().svg_workspace_bytes(C.byref(shape), int(t)))
+
+
+def svg_tile_counts(shape: SvgShape):
+    nq, nk = C.c_int32(), C.c_int32()
+    _check(lib().svg_tile_counts(C.byref(shape), C.byref(nq), C.byref(nk)), "svg_tile_counts")
+    return nq.value, nk.value
+
+
+def svg_tile_list_build(shape: SvgShape, pattern: int):
+    """Host CSR (row_ptr int32[nq+1], col_idx int32[nnz]) as numpy arrays."""
+    nq, _ = svg_tile_counts(shape)
+    row_ptr = np.zeros(nq + 1, dtype=np.int32)
+    nnz = C.c_int64()
+    _check(lib().svg_tile_list_build(C.byref(shape), int(pattern), row_ptr.ctypes.data, None, 0,
+                                     C.byref(nnz)), "svg_tile_list_build")
+    col_idx = np.zeros(max(nnz.value, 1), dtype=np.int32)
+    _check(lib().svg_tile_list_build(C.byref(shape), int(pattern), row_ptr.ctypes.data,
+                                     col_idx.ctypes.data, nnz.value, C.byref(nnz)),
+           "svg_tile_list_build")
+    return row_ptr, col_idx[:nnz.value]
+
+
+def svg_profile_heads(shape, q, k, v, rows, t, labels, mse, workspace, workspace_bytes, stream=None):
+    _check(lib().svg_profile_heads(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(rows), int(t),
+                                   _ptr(labels), _ptr(mse), _ptr(workspace), int(workspace_bytes),
+                                   _stream(stream)), "svg_profile_heads")
+
+
+def svg_layout_fwd(shape, x, out, labels=None, stream=None):
+    _check(lib().svg_layout_fwd(C.byref(shape), _ptr(x), _ptr(out), _ptr(labels), _stream(stream)),
+           "svg_layout_fwd")
+
+
+def svg_layout_inv(shape, x, out, labels=None, stream=None):
+    _check(lib().svg_layout_inv(C.byref(shape), _ptr(x), _ptr(out), _ptr(labels), _stream(stream)),
+           "svg_layout_inv")
+
+
+def svg_sparse_attn_fwd(shape, q, k, v, o, labels, row_ptr_s, col_idx_s, row_ptr_t, col_idx_t,
+                        workspace=None, workspace_bytes=0, stream=None):
+    _check(lib().svg_sparse_attn_fwd(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(labels),
+                                     _ptr(row_ptr_s), _ptr(col_idx_s), _ptr(row_ptr_t),
+                                     _ptr(col_idx_t), _ptr(workspace), int(workspace_bytes),
+                                     _stream(stream)), "svg_sparse_attn_fwd")
+
+
+def svg_dense_attn_fwd(shape, q, k, v, o, workspace=None, workspace_bytes=0, stream=None):
+    _check(lib().svg_dense_attn_fwd(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(o),
+                                    _ptr(workspace), int(workspace_bytes), _stream(stream)),
+           "svg_dense_attn_fwd")

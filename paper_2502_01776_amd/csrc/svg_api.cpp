@@ -1,0 +1,96 @@
+// C-ABI entry points that enqueue kernels: argument checks, then the launchers.
+#include "svg_internal.h"
+
+using svg::Geo;
+
+namespace {
+
+size_t tensor_bytes(const Geo& g) { return (size_t)g.B * g.H * g.N * g.D * 2; }
+
+bool overlap(const void* a, const void* b, size_t bytes) {
+  const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
+  return x < y + bytes && y < x + bytes;
+}
+
+int check_qkvo(const void* q, const void* k, const void* v, const void* o) {
+  if (!q || !k || !v || !o) return SVG_ERR_INVALID_ARG;
+  if (svg::misaligned16(q) || svg::misaligned16(k) || svg::misaligned16(v) || svg::misaligned16(o))
+    return SVG_ERR_INVALID_ARG;
+  return SVG_OK;
+}
+
+int layout_call(const svg_shape_t* shape, const void* in, void* out, const uint8_t* labels,
+                void* stream, bool inverse) {
+  Geo g;
+  int rc = svg::make_geo(shape, &g);
+  if (rc != SVG_OK) return rc;
+  if (!in || !out || svg::misaligned16(in) || svg::misaligned16(out)) return SVG_ERR_INVALID_ARG;
+  if (overlap(in, out, tensor_bytes(g))) return SVG_ERR_ALIAS;
+  return svg::launch_layout(g, in, out, labels, inverse, static_cast<hipStream_t>(stream));
+}
+
+}  // namespace
+
+extern "C" {
+
+int svg_layout_fwd(const svg_shape_t* shape, const void* in, void* out, const uint8_t* labels,
+                   void* stream) {
+  return layout_call(shape, in, out, labels, stream, false);
+}
+
+int svg_layout_inv(const svg_shape_t* shape, const void* in, void* out, const uint8_t* labels,
+                   void* stream) {
+  return layout_call(shape, in, out, labels, stream, true);
+}
+
+int svg_profile_heads(const svg_shape_t* shape, const void* q, const void* k, const void* v,
+                      const int32_t* rows, int32_t t, uint8_t* labels, float* mse, void* workspace,
+                      size_t workspace_bytes, void* stream) {
+  Geo g;
+  int rc = svg::make_geo(shape, &g);
+  if (rc != SVG_OK) return rc;
+  if (!q || !k || !v || !rows || !labels || t <= 0) return SVG_ERR_INVALID_ARG;
+  if (svg::misaligned16(q) || svg::misaligned16(k) || svg::misaligned16(v)) return SVG_ERR_INVALID_ARG;
+  if ((int64_t)3 * g.B * g.H * ((t + g.bm - 1) / g.bm) > (int64_t)1 << 30) return SVG_ERR_UNSUPPORTED;
+  if (!workspace || workspace_bytes < svg_workspace_bytes(shape, t)) return SVG_ERR_WORKSPACE;
+  if (svg::misaligned16(workspace)) return SVG_ERR_INVALID_ARG;
+  return svg::launch_profile(g, q, k, v, rows, t, labels, mse, static_cast<float*>(workspace),
+                             static_cast<hipStream_t>(stream));
+}
+
+int svg_sparse_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, const void* v,
+                        void* o, const uint8_t* labels, const int32_t* row_ptr_s,
+                        const int32_t* col_idx_s, const int32_t* row_ptr_t,
+                        const int32_t* col_idx_t, void* workspace, size_t workspace_bytes,
+                        void* stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  Geo g;
+  int rc = svg::make_geo(shape, &g);
+  if (rc != SVG_OK) return rc;
+  rc = check_qkvo(q, k, v, o);
+  if (rc != SVG_OK) return rc;
+  if (!row_ptr_s || !col_idx_s) return SVG_ERR_INVALID_ARG;
+  if (labels && (!row_ptr_t || !col_idx_t)) return SVG_ERR_INVALID_ARG;
+  const size_t bytes = tensor_bytes(g);
+  if (overlap(o, q, bytes) || overlap(o, k, bytes) || overlap(o, v, bytes)) return SVG_ERR_ALIAS;
+  return svg::launch_attention(g, q, k, v, o, labels, row_ptr_s, col_idx_s, row_ptr_t, col_idx_t,
+                               true, static_cast<hipStream_t>(stream));
+}
+
+int svg_dense_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, const void* v,
+                       void* o, void* workspace, size_t workspace_bytes, void* stream) {
+  (void)workspace;
+  (void)workspace_bytes;
+  Geo g;
+  int rc = svg::make_geo(shape, &g);
+  if (rc != SVG_OK) return rc;
+  rc = check_qkvo(q, k, v, o);
+  if (rc != SVG_OK) return rc;
+  const size_t bytes = tensor_bytes(g);
+  if (overlap(o, q, bytes) || overlap(o, k, bytes) || overlap(o, v, bytes)) return SVG_ERR_ALIAS;
+  return svg::launch_attention(g, q, k, v, o, nullptr, nullptr, nullptr, nullptr, nullptr, false,
+                               static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

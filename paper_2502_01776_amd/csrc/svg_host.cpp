@@ -1,0 +1,145 @@
+// Host side of the C ABI: argument validation, error strings, and the kept-tile
+// list builder.  The tile list depends only on the geometry, so it is built on the
+// host in closed form (interval arithmetic on frame / position groups) and the
+// caller uploads it once per shape.
+#include <algorithm>
+#include <cmath>
+#include <vector>
+
+#include "svg_internal.h"
+
+namespace svg {
+
+int make_geo(const svg_shape_t* s, Geo* g) {
+  if (!s) return SVG_ERR_INVALID_ARG;
+  if (s->B <= 0 || s->H <= 0 || s->F <= 0 || s->P <= 0 || s->T < 0) return SVG_ERR_INVALID_ARG;
+  if (s->w_s < 0 || s->w_t < 0) return SVG_ERR_INVALID_ARG;
+  if (s->text_first != 0 && s->text_first != 1) return SVG_ERR_INVALID_ARG;
+  if (s->sink_first_frame != 0 && s->sink_first_frame != 1) return SVG_ERR_INVALID_ARG;
+  if (!(s->softmax_scale == s->softmax_scale) || std::isinf(s->softmax_scale)) return SVG_ERR_INVALID_ARG;
+  if (s->D != 64 && s->D != 128) return SVG_ERR_UNSUPPORTED;
+  const bool big = s->block_m == 128 && s->block_n == 64;
+  const bool small = s->block_m == 32 && s->block_n == 32;
+  if (!big && !small) return SVG_ERR_UNSUPPORTED;
+  const int64_t n = (int64_t)s->F * s->P + s->T;
+  // row indices, tile indices and B*H*nq must fit comfortably in int32
+  if (n > (1 << 22)) return SVG_ERR_UNSUPPORTED;
+  const int64_t nq = (n + s->block_m - 1) / s->block_m;
+  if ((int64_t)s->B * s->H * nq > (int64_t)1 << 30) return SVG_ERR_UNSUPPORTED;
+  g->B = s->B; g->H = s->H; g->F = s->F; g->P = s->P; g->T = s->T; g->D = s->D;
+  g->N = (int)n;
+  g->text_first = s->text_first;
+  g->off = s->text_first ? s->T : 0;
+  g->video_end = g->off + s->F * s->P;
+  g->w_s = s->w_s; g->w_t = s->w_t; g->sink = s->sink_first_frame;
+  g->bm = s->block_m; g->bn = s->block_n;
+  g->nq = (int)nq;
+  g->nk = (int)((n + s->block_n - 1) / s->block_n);
+  g->scale = s->softmax_scale > 0.f ? s->softmax_scale : 1.0f / std::sqrt((float)s->D);
+  return SVG_OK;
+}
+
+}  // namespace svg
+
+using svg::Geo;
+
+extern "C" {
+
+const char* svg_strerror(int status) {
+  switch (status) {
+    case SVG_OK: return "ok";
+    case SVG_ERR_INVALID_ARG: return "invalid argument";
+    case SVG_ERR_UNSUPPORTED: return "unsupported head dimension, tile shape or size";
+    case SVG_ERR_WORKSPACE: return "workspace missing or too small";
+    case SVG_ERR_ALIAS: return "input and output overlap";
+    case SVG_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+const char* svg_version(void) { return "0.1"; }
+
+size_t svg_workspace_bytes(const svg_shape_t* shape, int32_t t) {
+  Geo g;
+  if (svg::make_geo(shape, &g) != SVG_OK || t <= 0) return 0;
+  return (size_t)3 * g.B * g.H * (size_t)t * g.D * sizeof(float);
+}
+
+int svg_tile_counts(const svg_shape_t* shape, int32_t* nq, int32_t* nk) {
+  Geo g;
+  int rc = svg::make_geo(shape, &g);
+  if (rc != SVG_OK) return rc;
+  if (!nq || !nk) return SVG_ERR_INVALID_ARG;
+  *nq = g.nq;
+  *nk = g.nk;
+  return SVG_OK;
+}
+
+int svg_tile_list_build(const svg_shape_t* shape, int pattern, int32_t* row_ptr, int32_t* col_idx,
+                        int64_t cap, int64_t* nnz_out) {
+  Geo g;
+  int rc = svg::make_geo(shape, &g);
+  if (rc != SVG_OK) return rc;
+  if (pattern != SVG_HEAD_SPATIAL && pattern != SVG_HEAD_TEMPORAL) return SVG_ERR_INVALID_ARG;
+  if (!row_ptr || !nnz_out || (col_idx && cap < 0)) return SVG_ERR_INVALID_ARG;
+
+  // In its own order a pattern groups `unit` consecutive video rows: a frame (P rows)
+  // for spatial, a position (F rows) for temporal; `groups` of them; window w groups.
+  const int unit = pattern == SVG_HEAD_SPATIAL ? g.P : g.F;
+  const int groups = pattern == SVG_HEAD_SPATIAL ? g.F : g.P;
+  const int w = pattern == SVG_HEAD_SPATIAL ? g.w_s : g.w_t;
+  const int v0 = g.off, v1 = g.video_end;  // video rows [v0, v1)
+
+  std::vector<uint8_t> keep(g.nk);
+  // tiles kept by every video query: text keys, and frame-0 keys if the sink is on
+  std::vector<uint8_t> always(g.nk, 0);
+  auto mark = [&](std::vector<uint8_t>& m, int64_t lo, int64_t hi) {  // rows [lo, hi] inclusive
+    if (lo > hi) return;
+    for (int b = (int)(lo / g.bn); b <= (int)(hi / g.bn); ++b) m[b] = 1;
+  };
+  if (g.T > 0) {
+    if (g.text_first) mark(always, 0, g.T - 1); else mark(always, v1, g.N - 1);
+  }
+  if (g.sink) {
+    if (pattern == SVG_HEAD_SPATIAL) {
+      mark(always, v0, v0 + g.P - 1);
+    } else {
+      for (int b = 0; b < g.nk; ++b) {  // P-outer: frame-0 tokens sit at video offsets k*F
+        int64_t lo = std::max<int64_t>((int64_t)b * g.bn, v0) - v0;
+        int64_t hi = std::min<int64_t>((int64_t)(b + 1) * g.bn, v1) - 1 - v0;
+        if (lo <= hi && ((lo + g.F - 1) / g.F) * g.F <= hi) always[b] = 1;
+      }
+    }
+  }
+
+  int64_t nnz = 0;
+  bool overflow = false;
+  row_ptr[0] = 0;
+  for (int a = 0; a < g.nq; ++a) {
+    const int64_t r0 = (int64_t)a * g.bm;
+    const int64_t r1 = std::min<int64_t>(r0 + g.bm, g.N) - 1;
+    const bool has_text_query = g.T > 0 && (r0 < v0 || r1 >= v1);
+    if (has_text_query) {
+      std::fill(keep.begin(), keep.end(), (uint8_t)1);
+    } else {
+      keep = always;
+      const int64_t ga = (r0 - v0) / unit, gb = (r1 - v0) / unit;
+      const int64_t lo = v0 + std::max<int64_t>(0, ga - w) * unit;
+      const int64_t hi = v0 + std::min<int64_t>(groups, gb + w + 1) * unit - 1;
+      mark(keep, lo, hi);
+    }
+    for (int b = 0; b < g.nk; ++b) {
+      if (!keep[b]) continue;
+      if (col_idx) {
+        if (nnz < cap) col_idx[nnz] = b; else overflow = true;
+      }
+      ++nnz;
+    }
+    if (nnz > INT32_MAX) return SVG_ERR_UNSUPPORTED;
+    row_ptr[a + 1] = (int32_t)nnz;
+  }
+  *nnz_out = nnz;
+  return overflow ? SVG_ERR_INVALID_ARG : SVG_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,39 @@
+// Internal declarations shared by the host-side entry points and the kernel
+// launchers of the sparse 3D attention library.  Not part of the C ABI.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "svg.h"
+
+namespace svg {
+
+// Geometry after validation, passed by value to kernels.
+struct Geo {
+  int B, H, F, P, T, D, N;
+  int off;          // first video row: T if text_first else 0
+  int video_end;    // off + F*P
+  int w_s, w_t, sink;
+  int bm, bn, nq, nk;
+  int text_first;
+  float scale;      // softmax scale
+};
+
+// Checks sizes, D and tile shape.  Returns SVG_OK and fills g, or an error code.
+int make_geo(const svg_shape_t* s, Geo* g);
+
+inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+inline int hip_status(hipError_t e) { return e == hipSuccess ? SVG_OK : SVG_ERR_HIP; }
+
+// Kernel launchers (defined in the .hip files).  All arguments validated by the caller.
+int launch_layout(const Geo& g, const void* in, void* out, const uint8_t* labels, bool inverse,
+                  hipStream_t stream);
+int launch_attention(const Geo& g, const void* q, const void* k, const void* v, void* o,
+                     const uint8_t* labels, const int32_t* row_ptr_s, const int32_t* col_idx_s,
+                     const int32_t* row_ptr_t, const int32_t* col_idx_t, bool sparse,
+                     hipStream_t stream);
+int launch_profile(const Geo& g, const void* q, const void* k, const void* v, const int32_t* rows,
+                   int t, uint8_t* labels, float* mse, float* workspace, hipStream_t stream);
+
+}  // namespace svg

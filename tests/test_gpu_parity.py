@@ -1,0 +1,219 @@
+"""GPU parity: every entry point of the library against the CPU oracle, element by
+element on seeded inputs that span several tiles and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2502_01776_amd as S
+from oracle import svg_oracle as O
+from workloads import get_config, make_qkv, make_plain_qkv, sample_rows, planted_labels
+from helpers import (f64, bits, dev_i32, device_tile_lists, gpu_profile, gpu_layer, assert_attn_close,
+                     labels_match)
+
+pytestmark = pytest.mark.gpu
+
+SMALL = ["tiny", "mid64", "mid128"]
+
+
+def setup(name, **ov):
+    cfg = get_config(name, **ov)
+    return cfg, S.shape_from_config(cfg), O.Geometry.from_config(cfg)
+
+
+# ------------------------------------------------------------------ layout
+@pytest.mark.parametrize("name", SMALL)
+@pytest.mark.parametrize("with_labels", [False, True])
+def test_layout_bit_exact(name, with_labels):
+    cfg, sh, g = setup(name)
+    q, _, _ = make_qkv(cfg)
+    x = q.cuda()
+    lab_np = planted_labels(cfg)
+    lab = torch.from_numpy(lab_np).cuda() if with_labels else None
+    y = torch.zeros_like(x)
+    S.svg_layout_fwd(sh, x, y, lab)
+    back = torch.zeros_like(x)
+    S.svg_layout_inv(sh, y, back, lab)
+    torch.cuda.synchronize()
+    xb = bits(x)
+    ref = O.layout_fwd(xb, g)
+    if with_labels:
+        sp = (lab_np.reshape(g.B, g.H) == 0)
+        ref[sp] = xb[sp]
+    assert np.array_equal(bits(y), ref)
+    assert np.array_equal(bits(back), xb)
+
+
+# ------------------------------------------------------------------ dense
+@pytest.mark.parametrize("name", SMALL)
+def test_dense_attention(name):
+    cfg, sh, g = setup(name)
+    q, k, v = make_qkv(cfg)
+    o = torch.zeros_like(q).cuda()
+    S.svg_dense_attn_fwd(sh, q.cuda(), k.cuda(), v.cuda(), o)
+    torch.cuda.synchronize()
+    qd, kd, vd = f64(q), f64(k), f64(v)
+    for b in range(g.B):
+        for h in range(g.H):
+            ref = O.dense_attention_head(qd[b, h], kd[b, h], vd[b, h], g)
+            assert_attn_close(o[b, h], ref, f"{name} dense b{b} h{h}")
+
+
+# ------------------------------------------------------------------ block-sparse
+@pytest.mark.parametrize("name", SMALL)
+def test_sparse_attention_per_pattern(name):
+    """Both tile lists applied to every head in the order given (no layout step)."""
+    cfg, sh, g = setup(name)
+    q, k, v = make_qkv(cfg)
+    qd, kd, vd = f64(q), f64(k), f64(v)
+    lists = device_tile_lists(sh)
+    for pat in (0, 1):
+        lab = torch.full((g.B * g.H,), pat, dtype=torch.uint8, device="cuda")
+        o = torch.zeros_like(q).cuda()
+        S.svg_sparse_attn_fwd(sh, q.cuda(), k.cuda(), v.cuda(), o, lab, *lists)
+        torch.cuda.synchronize()
+        rp, ci = O.tile_list(g, pat)
+        for b in range(g.B):
+            for h in range(g.H):
+                ref = O.sparse_attention_head(qd[b, h], kd[b, h], vd[b, h], rp, ci, g)
+                assert_attn_close(o[b, h], ref, f"{name} pattern {pat} b{b} h{h}")
+
+
+def test_sparse_with_full_list_equals_dense_kernel_bitwise():
+    cfg, sh, g = setup("mid128")
+    q, k, v = (x.cuda() for x in make_qkv(cfg))
+    rp, ci = O.full_tile_list(g)
+    o1, o2 = torch.zeros_like(q), torch.zeros_like(q)
+    S.svg_sparse_attn_fwd(sh, q, k, v, o1, None, dev_i32(rp), dev_i32(ci), None, None)
+    S.svg_dense_attn_fwd(sh, q, k, v, o2)
+    torch.cuda.synchronize()
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
+
+
+def test_empty_tile_rows_give_zeros():
+    cfg, sh, g = setup("mid64")
+    q, k, v = (x.cuda() for x in make_qkv(cfg))
+    rp, ci = O.tile_list(g, 0)
+    rp2 = rp.copy()
+    n1 = rp[2] - rp[1]
+    rp2[2:] -= n1                      # query tile 1 keeps nothing
+    ci2 = np.concatenate([ci[:rp[1]], ci[rp[2]:]])
+    o = torch.full_like(q, 7.0)
+    S.svg_sparse_attn_fwd(sh, q, k, v, o, None, dev_i32(rp2), dev_i32(ci2), None, None)
+    torch.cuda.synchronize()
+    assert (o[:, :, 128:256] == 0).all()
+    ref = O.sparse_attention_head(f64(q)[0, 0], f64(k)[0, 0], f64(v)[0, 0], rp, ci, g)
+    assert_attn_close(o[0, 0, :128], ref[:128])
+    assert_attn_close(o[0, 0, 256:], ref[256:])
+
+
+# ------------------------------------------------------------------ profiling
+@pytest.mark.parametrize("name", SMALL)
+def test_profile_heads(name):
+    cfg, sh, g = setup(name)
+    q, k, v = make_qkv(cfg)
+    rows = sample_rows(cfg)
+    labels, mse = gpu_profile(sh, q.cuda(), k.cuda(), v.cuda(), rows)
+    omse, olab = O.profile_heads(f64(q), f64(k), f64(v), rows, g)
+    assert labels_match(labels, omse, olab)
+    assert np.array_equal(labels.cpu().numpy(), planted_labels(cfg))
+    got = mse.cpu().numpy().astype(np.float64).reshape(g.B, g.H, 2)
+    # bf16 rounding of the weights puts a noise floor under the measured errors
+    assert np.allclose(got, omse, rtol=0.05, atol=2e-5), (got, omse)
+
+
+def test_profile_row_set_spanning_several_query_tiles():
+    cfg, sh, g = setup("mid128")
+    q, k, v = make_qkv(cfg)
+    rows = sample_rows(cfg, t=300)          # 3 query tiles of 128, ragged
+    labels, mse = gpu_profile(sh, q.cuda(), k.cuda(), v.cuda(), rows)
+    omse, olab = O.profile_heads(f64(q), f64(k), f64(v), rows, g)
+    assert labels_match(labels, omse, olab)
+    assert np.allclose(mse.cpu().numpy().reshape(omse.shape), omse, rtol=0.05, atol=2e-5)
+
+
+def test_profile_with_sink_and_unstructured_heads():
+    cfg, sh, g = setup("mid64", sink_first_frame=1)
+    q, k, v = make_plain_qkv(cfg["B"], cfg["H"], cfg["N"], cfg["D"], seed=5)
+    rows = sample_rows(cfg, t=40)
+    labels, mse = gpu_profile(sh, q.cuda(), k.cuda(), v.cuda(), rows)
+    omse, olab = O.profile_heads(f64(q), f64(k), f64(v), rows, g)
+    assert labels_match(labels, omse, olab, rel=2e-2)
+    assert np.allclose(mse.cpu().numpy().reshape(omse.shape), omse, rtol=0.05, atol=2e-5)
+
+
+# ------------------------------------------------------------------ whole layer
+@pytest.mark.parametrize("name", SMALL)
+def test_whole_layer(name):
+    cfg, sh, g = setup(name)
+    q, k, v = make_qkv(cfg)
+    rows = sample_rows(cfg)
+    qc, kc, vc = q.cuda(), k.cuda(), v.cuda()
+    labels, _ = gpu_profile(sh, qc, kc, vc, rows)
+    o = gpu_layer(sh, qc, kc, vc, labels)
+    omse, olab = O.profile_heads(f64(q), f64(k), f64(v), rows, g)
+    assert np.array_equal(labels.cpu().numpy().reshape(g.B, g.H), olab)
+    ref = O.svg_attention_layer(f64(q), f64(k), f64(v), olab, g)
+    for b in range(g.B):
+        for h in range(g.H):
+            assert_attn_close(o[b, h], ref[b, h], f"{name} layer b{b} h{h}")
+
+
+def test_results_are_deterministic():
+    cfg, sh, g = setup("mid128")
+    q, k, v = (x.cuda() for x in make_qkv(cfg))
+    rows = sample_rows(cfg)
+    l1, m1 = gpu_profile(sh, q, k, v, rows)
+    l2, m2 = gpu_profile(sh, q, k, v, rows)
+    assert torch.equal(l1, l2) and torch.equal(m1, m2)
+    o1 = gpu_layer(sh, q, k, v, l1)
+    o2 = gpu_layer(sh, q, k, v, l1)
+    assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
+
+
+# ------------------------------------------------------------------ degenerate geometries
+@pytest.mark.parametrize("geo", [
+    dict(F=1, P=200, T=0, D=64),            # one frame, no text
+    dict(F=9, P=1, T=3, D=128),             # one token per frame
+    dict(F=2, P=5, T=0, D=64),              # N = 10, smaller than any tile
+    dict(F=3, P=64, T=64, D=128, text_first=0),   # tile-aligned everything
+    dict(F=4, P=33, T=1, D=64, text_first=0, sink_first_frame=1),
+])
+@pytest.mark.parametrize("blocks", [(128, 64), (32, 32)])
+def test_degenerate_geometries(geo, blocks):
+    base = dict(get_config("mid64"), B=1, H=2, w_s=1, w_t=2, text_first=1, sink_first_frame=0,
+                block_m=blocks[0], block_n=blocks[1], spatial_heads=[0])
+    base.update(geo)
+    base["N"] = base["F"] * base["P"] + base["T"]
+    cfg = base
+    sh, g = S.shape_from_config(cfg), O.Geometry.from_config(cfg)
+    q, k, v = make_plain_qkv(1, 2, g.N, g.D, seed=11)
+    qc, kc, vc = q.cuda(), k.cuda(), v.cuda()
+    # tile lists bit-exact
+    for pat in (0, 1):
+        rp, ci = S.svg_tile_list_build(sh, pat)
+        orp, oci = O.tile_list(g, pat)
+        assert np.array_equal(rp, orp) and np.array_equal(ci, oci)
+    rows = np.arange(0, g.N, max(1, g.N // 7), dtype=np.int32)
+    labels, mse = gpu_profile(sh, qc, kc, vc, rows)
+    omse, olab = O.profile_heads(f64(q), f64(k), f64(v), rows, g)
+    assert np.allclose(mse.cpu().numpy().reshape(omse.shape), omse, rtol=0.05, atol=2e-5)
+    lab = torch.tensor([0, 1], dtype=torch.uint8, device="cuda")
+    o = gpu_layer(sh, qc, kc, vc, lab)
+    ref = O.svg_attention_layer(f64(q), f64(k), f64(v), np.array([[0, 1]]), g)
+    for h in range(2):
+        assert_attn_close(o[0, h], ref[0, h], f"{geo} head {h}")
+    od = torch.zeros_like(qc)
+    S.svg_dense_attn_fwd(sh, qc, kc, vc, od)
+    torch.cuda.synchronize()
+    assert_attn_close(od[0, 0], O.dense_attention_head(f64(q)[0, 0], f64(k)[0, 0], f64(v)[0, 0], g))
+
+
+def test_large_logits_do_not_overflow():
+    """Row maxima far from zero (|logit| ~ 60): the online softmax must stay finite."""
+    cfg, sh, g = setup("mid64")
+    q, k, v = make_qkv(cfg, boost_nats=60.0)
+    o = torch.zeros_like(q).cuda()
+    S.svg_dense_attn_fwd(sh, q.cuda(), k.cuda(), v.cuda(), o)
+    torch.cuda.synchronize()
+    ref = O.dense_attention_head(f64(q)[0, 1], f64(k)[0, 1], f64(v)[0, 1], g)
+    assert_attn_close(o[0, 1], ref, "boost 60")
