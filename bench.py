@@ -1,0 +1,249 @@
+#!/usr/bin/env python3
+"""Benchmark of the sparse 3D attention layer on one MI355X.
+
+A step is one pass of the whole hot path over one synthetic layer input that is
+already resident in HBM: online profiling (three masked attentions over the
+sampled rows + MSE + label), layout transform of q, k, v, block-sparse attention
+over the kept tiles, inverse layout transform of o.  The in-library dense
+attention is timed beside it, and the CPU oracle is timed on a bounded sample.
+
+Prints ONE JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
+PEAK_HBM_GBS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="hunyuan_skip85")
+    ap.add_argument("--dense-reps", type=int, default=3)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--only", default="", help="time a single stage only (profile|layout|sparse|dense); "
+                    "used for per-kernel rocprofv3 runs")
+    return ap.parse_args()
+
+
+def ev():
+    import torch
+    return torch.cuda.Event(enable_timing=True)
+
+
+def cpu_baseline(cfg, q, k, v, rows, labels_np, nnz_total):
+    """Oracle timed on a bounded sample of the same workload: profiling of one head on
+    a subset of the sampled rows, and the block-sparse pass of a few query tiles of
+    one spatial and one temporal head.  Extrapolated linearly to one layer."""
+    import numpy as np
+    import torch
+    from oracle import svg_oracle as O
+    g = O.Geometry.from_config(cfg)
+    nq, nk = O.n_tiles(g)
+    threads = torch.get_num_threads()
+    f64 = lambda x: x.cpu().to(torch.float64).numpy()
+    h_s = int(np.argmax(labels_np == 0)) if (labels_np == 0).any() else 0
+    h_t = int(np.argmax(labels_np == 1)) if (labels_np == 1).any() else 0
+    budget_rows = max(8, min(len(rows), int(2.0e8 // g.N)))      # bounds the t x N score matrices
+    sub = rows[:: max(1, len(rows) // budget_rows)][:budget_rows]
+    t0 = time.perf_counter()
+    g1 = O.Geometry(**{**g.__dict__, "B": 1, "H": 1})
+    O.profile_heads(f64(q[0, h_s])[None, None], f64(k[0, h_s])[None, None], f64(v[0, h_s])[None, None],
+                    sub, g1)
+    t_prof = time.perf_counter() - t0
+    prof_layer_s = t_prof / len(sub) * len(rows) * g.B * g.H
+
+    tiles_done, t_attn = 0, 0.0
+    n_sample = 4
+    for pat, h in ((O.SPATIAL, h_s), (O.TEMPORAL, h_t)):
+        qh, kh, vh = f64(q[0, h]), f64(k[0, h]), f64(v[0, h])
+        pick = sorted(set(int(x) for x in np.linspace(0, nq - 1, n_sample + 2)[1:-1]))
+        t0 = time.perf_counter()
+        if pat == O.TEMPORAL:
+            qh, kh, vh = O.layout_fwd(qh, g), O.layout_fwd(kh, g), O.layout_fwd(vh, g)
+        rp = np.zeros(nq + 1, dtype=np.int64)
+        cols = []
+        for a in range(nq):
+            c = O.kept_tiles_of_row(g, pat, a) if a in pick else np.zeros(0, np.int32)
+            cols.append(c)
+            rp[a + 1] = rp[a] + len(c)
+            tiles_done += len(c)
+        O.sparse_attention_head(qh, kh, vh, rp, np.concatenate(cols), g, q_tiles=pick)
+        t_attn += time.perf_counter() - t0
+    attn_layer_s = t_attn / max(tiles_done, 1) * nnz_total
+    layer_s = prof_layer_s + attn_layer_s
+    dense_flops = 4.0 * g.N * g.N * g.D * g.H * g.B
+    return {
+        "value": dense_flops / layer_s / 1e12, "unit": "TFLOP/s (effective)", "cores": threads,
+        "kind": "oracle", "extrapolated": True, "ms_per_layer": layer_s * 1e3,
+        "sample": (f"fp64 numpy oracle: profiling of 1 head on {len(sub)} of {len(rows)} sampled rows "
+                   f"({t_prof:.1f} s) + block-sparse pass of {n_sample} query tiles of one spatial and "
+                   f"one temporal head incl. tile-list rows and layout ({t_attn:.1f} s, {tiles_done} "
+                   f"tiles); scaled linearly to {g.B * g.H} heads, {len(rows)} rows, {nnz_total} tiles"),
+    }
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (heads would shard across GPUs without any "
+              "exchange inside the path, but no multi-GPU run is part of it); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+    import paper_2502_01776_amd as S
+    from workloads import get_config, make_qkv, sample_rows
+
+    S.lib()                                   # fail loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        raise SystemExit("bench.py needs a GPU (no CPU fallback exists)")
+    cfg = get_config(args.workload)
+    sh = S.shape_from_config(cfg)
+    B, H, N, D = cfg["B"], cfg["H"], cfg["N"], cfg["D"]
+    BH = B * H
+
+    q, k, v = make_qkv(cfg, device="cuda")
+    rows_np = sample_rows(cfg)
+    t = len(rows_np)
+    rows = torch.from_numpy(rows_np).cuda()
+    lists_np = [S.svg_tile_list_build(sh, p) for p in (0, 1)]
+    lists = []
+    for rp, ci in lists_np:
+        lists += [torch.from_numpy(rp).cuda(), torch.from_numpy(ci).cuda()]
+    nq, nk = S.svg_tile_counts(sh)
+    ws_bytes = S.svg_workspace_bytes(sh, t)
+    ws = torch.empty(ws_bytes, dtype=torch.uint8, device="cuda")
+    labels = torch.zeros(BH, dtype=torch.uint8, device="cuda")
+    mse = torch.zeros(BH, 2, dtype=torch.float32, device="cuda")
+    qp, kp, vp, op, o = (torch.empty_like(q) for _ in range(5))
+
+    def stage_profile():
+        S.svg_profile_heads(sh, q, k, v, rows, t, labels, mse, ws, ws_bytes)
+
+    def stage_layout_fwd():
+        S.svg_layout_fwd(sh, q, qp, labels)
+        S.svg_layout_fwd(sh, k, kp, labels)
+        S.svg_layout_fwd(sh, v, vp, labels)
+
+    def stage_sparse():
+        S.svg_sparse_attn_fwd(sh, qp, kp, vp, op, labels, *lists)
+
+    def stage_layout_inv():
+        S.svg_layout_inv(sh, op, o, labels)
+
+    stages = [("profile", stage_profile), ("layout_fwd", stage_layout_fwd),
+              ("sparse_attn", stage_sparse), ("layout_inv", stage_layout_inv)]
+
+    def step(marks=None):
+        for name, fn in stages:
+            if marks is not None:
+                e0, e1 = ev(), ev()
+                e0.record()
+                fn()
+                e1.record()
+                marks.setdefault(name, []).append((e0, e1))
+            else:
+                fn()
+
+    if args.only:
+        # single-stage mode for per-kernel profiling
+        step()
+        torch.cuda.synchronize()
+        fn = {"profile": stage_profile, "layout": lambda: (stage_layout_fwd(), stage_layout_inv()),
+              "sparse": stage_sparse,
+              "dense": lambda: S.svg_dense_attn_fwd(sh, q, k, v, o)}[args.only]
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            fn()
+        torch.cuda.synchronize()
+        print(json.dumps({"only": args.only, "workload": args.workload,
+                          "ms": (time.perf_counter() - t0) * 1e3 / args.steps}))
+        return
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    marks = {}
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(marks)
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    breakdown = {name: float(np.mean([a.elapsed_time(b) for a, b in lst])) for name, lst in marks.items()}
+
+    labels_np = labels.cpu().numpy()
+    n_temporal = int(labels_np.sum())
+    nnz = [int(rp[-1]) for rp, _ in lists_np]
+    nnz_total = (BH - n_temporal) * nnz[0] + n_temporal * nnz[1]
+    kept_fraction = nnz_total / (BH * nq * nk)
+
+    dense_ms = None
+    if not args.no_dense:
+        od = op        # reuse a buffer
+        S.svg_dense_attn_fwd(sh, q, k, v, od)
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(args.dense_reps):
+            S.svg_dense_attn_fwd(sh, q, k, v, od)
+        e1.record()
+        torch.cuda.synchronize()
+        dense_ms = e0.elapsed_time(e1) / args.dense_reps
+
+    dense_flops = 4.0 * N * N * D * BH
+    tile_flops = 4.0 * cfg["block_m"] * cfg["block_n"] * D
+    sparse_ms = breakdown["sparse_attn"]
+    achieved = tile_flops * nnz_total / (sparse_ms * 1e-3) / 1e12
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.workload}.json")
+    if os.path.exists(tpath):
+        with open(tpath) as f:
+            traffic = json.load(f).get("sparse_attn_bytes_per_launch")
+    layout_bytes = 2.0 * n_temporal * N * D * 2 + 2.0 * (BH - n_temporal) * N * D * 2   # read + write, all heads
+    out = {
+        "metric": "effective TFLOP/s of one sparse attention layer at %dk tokens "
+                  "(4*N^2*D*H / ms per layer; profile + layout + block-sparse attention + inverse layout)"
+                  % round(N / 1000),
+        "value": dense_flops / (wall_ms * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": wall_ms, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": args.workload, "B": B, "H": H, "F": cfg["F"], "P": cfg["P"], "T": cfg["T"],
+                   "N": N, "D": D, "w_s": cfg["w_s"], "w_t": cfg["w_t"], "tile": [cfg["block_m"], cfg["block_n"]],
+                   "profiled_rows": t, "temporal_heads": n_temporal, "kept_tile_fraction": kept_fraction},
+        "ms_per_layer": wall_ms,
+        "breakdown_ms": breakdown,
+        "dense_ms": dense_ms,
+        "dense_tflops": None if dense_ms is None else dense_flops / (dense_ms * 1e-3) / 1e12,
+        "speedup_vs_dense": None if dense_ms is None else dense_ms / wall_ms,
+        "layout_gbs": {"fwd_qkv": 3 * layout_bytes / (breakdown["layout_fwd"] * 1e-3) / 1e9,
+                       "inv_o": layout_bytes / (breakdown["layout_inv"] * 1e-3) / 1e9},
+        "profile_tflops": 3 * 4.0 * t * N * D * BH / (breakdown["profile"] * 1e-3) / 1e12,
+        "roofline": {"kernel": "attn_kernel<128,4,64,sparse>" if D == 128 else "attn_kernel<64,4,64,sparse>",
+                     "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, rows_np, labels_np, nnz_total)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

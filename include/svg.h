@@ -59,6 +59,10 @@ typedef enum svg_status {
 /* Text for a status code; never NULL. */
 const char* svg_strerror(int status);
 
+/* Text of the HIP error behind the calling thread's most recent SVG_ERR_HIP
+ * ("no error" if there was none). */
+const char* svg_last_hip_error(void);
+
 /* Library version, "major.minor". */
 const char* svg_version(void);
 

@@ -10,6 +10,7 @@ import ctypes as C
 import os
 
 import numpy as np
+import torch  # noqa: F401  -- must come first: the library binds to the HIP runtime torch has loaded
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libsvg_gfx950.so")
@@ -18,7 +19,7 @@ SVG_HEAD_SPATIAL = 0
 SVG_HEAD_TEMPORAL = 1
 SVG_OK = 0
 
-EXPORTS = ("svg_strerror", "svg_version", "svg_workspace_bytes", "svg_tile_counts",
+EXPORTS = ("svg_strerror", "svg_version", "svg_last_hip_error", "svg_workspace_bytes", "svg_tile_counts",
            "svg_tile_list_build", "svg_profile_heads", "svg_layout_fwd", "svg_layout_inv",
            "svg_sparse_attn_fwd", "svg_dense_attn_fwd")
 
@@ -37,7 +38,8 @@ class SvgShape(C.Structure):
 class SvgError(RuntimeError):
     def __init__(self, status, where):
         self.status = status
-        super().__init__(f"{where}: {svg_strerror(status)} ({status})")
+        detail = f": {lib().svg_last_hip_error().decode()}" if status == -5 else ""
+        super().__init__(f"{where}: {svg_strerror(status)} ({status}){detail}")
 
 
 _lib = None
@@ -58,6 +60,8 @@ def lib():
         L.svg_strerror.argtypes = [C.c_int]
         L.svg_version.restype = C.c_char_p
         L.svg_version.argtypes = []
+        L.svg_last_hip_error.restype = C.c_char_p
+        L.svg_last_hip_error.argtypes = []
         L.svg_workspace_bytes.restype = C.c_size_t
         L.svg_workspace_bytes.argtypes = [sp, C.c_int32]
         L.svg_tile_counts.restype = C.c_int
@@ -104,7 +108,6 @@ def _ptr(x):
 
 def _stream(stream):
     if stream is None:
-        import torch
         return torch.cuda.current_stream().cuda_stream
     if isinstance(stream, int):
         return stream

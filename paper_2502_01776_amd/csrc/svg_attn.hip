@@ -427,6 +427,7 @@ __global__ __launch_bounds__(256) void profile_finalize_kernel(const float* ws, 
 template <int D, int NW, int BN, int MODE>
 int launch_one(const AttnArgs& a, hipStream_t stream) {
   const unsigned grid = (unsigned)(((a.total + 7) / 8) * 8);
+  (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
   hipLaunchKernelGGL((attn_kernel<D, NW, BN, MODE>), dim3(grid), dim3(64 * NW), 0, stream, a);
   return hip_status(hipGetLastError());
 }
@@ -478,6 +479,7 @@ int launch_profile(const Geo& g, const void* q, const void* k, const void* v, co
   a.total = 3 * a.BH * a.nqt;
   int rc = dispatch<kProfile>(g, a, stream);
   if (rc != SVG_OK) return rc;
+  (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
   hipLaunchKernelGGL(profile_finalize_kernel, dim3(a.BH), dim3(256), 0, stream, workspace, a.BH, t,
                      g.D, labels, mse);
   return hip_status(hipGetLastError());

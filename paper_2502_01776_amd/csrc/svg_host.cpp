@@ -10,6 +10,9 @@
 
 namespace svg {
 
+static thread_local hipError_t g_last_hip_error = hipSuccess;
+void note_hip_error(hipError_t e) { g_last_hip_error = e; }
+
 int make_geo(const svg_shape_t* s, Geo* g) {
   if (!s) return SVG_ERR_INVALID_ARG;
   if (s->B <= 0 || s->H <= 0 || s->F <= 0 || s->P <= 0 || s->T < 0) return SVG_ERR_INVALID_ARG;
@@ -58,6 +61,8 @@ const char* svg_strerror(int status) {
 }
 
 const char* svg_version(void) { return "0.1"; }
+
+const char* svg_last_hip_error(void) { return hipGetErrorString(svg::g_last_hip_error); }
 
 size_t svg_workspace_bytes(const svg_shape_t* shape, int32_t t) {
   Geo g;

@@ -24,7 +24,13 @@ int make_geo(const svg_shape_t* s, Geo* g);
 
 inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
-inline int hip_status(hipError_t e) { return e == hipSuccess ? SVG_OK : SVG_ERR_HIP; }
+// Remembers the most recent HIP error of the calling thread for svg_last_hip_error().
+void note_hip_error(hipError_t e);
+inline int hip_status(hipError_t e) {
+  if (e == hipSuccess) return SVG_OK;
+  note_hip_error(e);
+  return SVG_ERR_HIP;
+}
 
 // Kernel launchers (defined in the .hip files).  All arguments validated by the caller.
 int launch_layout(const Geo& g, const void* in, void* out, const uint8_t* labels, bool inverse,

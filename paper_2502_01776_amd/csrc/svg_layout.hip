@@ -77,6 +77,7 @@ int launch_layout(const Geo& g, const void* in, void* out, const uint8_t* labels
   const int rows_per_block = (kThreads >> a.chunks_log2) * kRowsPerThread;
   dim3 grid((g.N + rows_per_block - 1) / rows_per_block, g.B * g.H);
   if (grid.y > 65535u) return SVG_ERR_UNSUPPORTED;
+  (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
   hipLaunchKernelGGL(layout_kernel, grid, dim3(kThreads), 0, stream, a);
   return hip_status(hipGetLastError());
 }

@@ -85,13 +85,14 @@ def planted_labels(cfg) -> np.ndarray:
 
 
 def _unit_rows(gen, n, D):
-    x = torch.randn(n, D, generator=gen, dtype=torch.float32)
+    x = torch.randn(n, D, generator=gen, dtype=torch.float32, device=gen.device)
     return x / x.norm(dim=1, keepdim=True)
 
 
 def make_qkv(cfg, boost_nats: float | None = 12.0, amplitude: float | None = None,
-             seed: int | None = None):
-    """bf16 CPU tensors q, k, v of shape [B,H,N,D].
+             seed: int | None = None, device: str = "cpu"):
+    """bf16 tensors q, k, v of shape [B,H,N,D] on `device` (the random stream, and so
+    the values, depend on the device the generator lives on).
 
     Every entry is sigma * N(0,1).  In heads listed in cfg['spatial_heads'] a unit
     vector chosen per frame is added to q and k of all video tokens of that frame;
@@ -103,9 +104,9 @@ def make_qkv(cfg, boost_nats: float | None = 12.0, amplitude: float | None = Non
     B, H, F, P, T, D, N = (cfg[k] for k in ("B", "H", "F", "P", "T", "D", "N"))
     if amplitude is None:
         amplitude = math.sqrt(boost_nats * math.sqrt(D))
-    gen = torch.Generator().manual_seed(cfg["seed"] if seed is None else seed)
+    gen = torch.Generator(device=device).manual_seed(cfg["seed"] if seed is None else seed)
     off = T if cfg["text_first"] else 0
-    q = torch.empty(B, H, N, D, dtype=torch.bfloat16)
+    q = torch.empty(B, H, N, D, dtype=torch.bfloat16, device=device)
     k = torch.empty_like(q)
     v = torch.empty_like(q)
     spatial = set(cfg["spatial_heads"])
@@ -118,7 +119,7 @@ def make_qkv(cfg, boost_nats: float | None = 12.0, amplitude: float | None = Non
                 e = _unit_rows(gen, P, D)                       # one per position
                 add = e[None, :, :].expand(F, P, D).reshape(F * P, D)
             for dst, planted in ((q, True), (k, True), (v, False)):
-                x = torch.randn(N, D, generator=gen, dtype=torch.float32) * cfg["sigma"]
+                x = torch.randn(N, D, generator=gen, dtype=torch.float32, device=device) * cfg["sigma"]
                 if planted:
                     x[off:off + F * P] += amplitude * add
                 dst[b, h] = x.to(torch.bfloat16)
