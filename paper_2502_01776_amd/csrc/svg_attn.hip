@@ -37,12 +37,15 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 enum Mode { kDense = 0, kSparse = 1, kProfile = 2 };
 
 constexpr int kCodeDrop = 0x7fffffff;   // key beyond N: never kept
 constexpr int kCodeKeep = 0x7ffffffe;   // text key / sink key: kept by every query
 constexpr float kNegBig = -1.0e30f;     // finite stand-in for -inf as the initial row maximum
+constexpr float kLazyLog2 = 8.0f;       // exponentials may reach 2^8 before the maximum is raised
 
 struct AttnArgs {
   const __bf16* q;
@@ -59,6 +62,7 @@ struct AttnArgs {
   int reverse_q;              // process query tiles last-to-first (heavy text-suffix tiles first)
   int total;                  // logical workgroups
   float scale_log2;           // softmax scale * log2(e)
+  float lazy_tau;             // raw-logit margin below which the running maximum is not raised
   int off, video_end, F, P, w_s, w_t, sink;
 };
 
@@ -69,9 +73,18 @@ __device__ __forceinline__ int k_swizzle(int key) {
   return D == 128 ? (key & 15) : ((key >> 1) & 7);
 }
 
-__device__ __forceinline__ float other_half(float x) {
-  // value held by lane l^32 (the lane that owns the other 16 keys of the same query)
-  return __shfl_xor(x, 32, 64);
+// Lanes l and l^32 own the two halves of one query's keys.  v_permlane32_swap with
+// both operands equal returns {x[l % 32], x[32 + l % 32]} in every lane, so the
+// combined maximum / sum needs no LDS traffic.
+__device__ __forceinline__ float both_halves_max(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+__device__ __forceinline__ float both_halves_sum(float x) {
+  const unsigned u = __float_as_uint(x);
+  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
 template <int D, int NW, int BN, int MODE>
@@ -87,7 +100,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   constexpr int V_UNITS = (BN / 4) * CPR;   // a unit = 4 keys x 8 channels
   constexpr int V_PER_THREAD = (V_UNITS + THREADS - 1) / THREADS;
   constexpr int K_BYTES = BN * D * 2;
-  constexpr int STAGE_BYTES = 2 * K_BYTES;
+  // V^T staging: [key/4][d][4 keys] with each key-group row padded by 128 bytes, so
+  // that the two half-waves of a ds_read_b64 (key groups kg and kg+1) fall on
+  // different banks.
+  constexpr int V_ROW = D * 8 + 128;
+  constexpr int V_BYTES = (BN / 4) * V_ROW;
+  constexpr int STAGE_BYTES = K_BYTES + V_BYTES;
   static_assert(K_PIECES % THREADS == 0, "K tile must split evenly over the workgroup");
 
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE_BYTES];
@@ -169,8 +187,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   float m_run = kNegBig;   // running row maximum (raw logits, before scaling)
   float l_run = 0.f;       // this lane's share of the running row sum
 
-  uint4 kst[K_PER_THREAD];
-  uint4 vst[V_PER_THREAD][4];
+  u32x4 kst[K_PER_THREAD];
+  u32x4 vst[V_PER_THREAD][4];
 
   auto load_tile = [&](int col) {
     const int key0 = col * BN;
@@ -179,7 +197,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
       const int u = tid + i * THREADS;
       const int key = u / CPR, c = u % CPR;
       const int krow = min(key0 + key, a.N - 1);
-      kst[i] = *reinterpret_cast<const uint4*>(kh + (size_t)krow * D + c * 8);
+      kst[i] = *reinterpret_cast<const u32x4*>(kh + (size_t)krow * D + c * 8);
     }
 #pragma unroll
     for (int i = 0; i < V_PER_THREAD; ++i) {
@@ -189,7 +207,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
 #pragma unroll
         for (int rr = 0; rr < 4; ++rr) {
           const int vrow = min(key0 + kg * 4 + rr, a.N - 1);
-          vst[i][rr] = *reinterpret_cast<const uint4*>(vh + (size_t)vrow * D + c * 8);
+          vst[i][rr] = *reinterpret_cast<const u32x4*>(vh + (size_t)vrow * D + c * 8);
         }
       }
     }
@@ -202,30 +220,28 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     for (int i = 0; i < K_PER_THREAD; ++i) {
       const int u = tid + i * THREADS;
       const int key = u / CPR, c = u % CPR;
-      *reinterpret_cast<uint4*>(kb + key * (D * 2) + ((c ^ k_swizzle<D>(key)) << 4)) = kst[i];
+      *reinterpret_cast<u32x4*>(kb + key * (D * 2) + ((c ^ k_swizzle<D>(key)) << 4)) = kst[i];
     }
 #pragma unroll
     for (int i = 0; i < V_PER_THREAD; ++i) {
       const int u = tid + i * THREADS;
       if (V_UNITS % THREADS == 0 || u < V_UNITS) {
         const int kg = u / CPR, c = u % CPR;
-        // 4 keys x 8 channels -> 8 channels x 4 keys
-        const unsigned* r0 = reinterpret_cast<const unsigned*>(&vst[i][0]);
-        const unsigned* r1 = reinterpret_cast<const unsigned*>(&vst[i][1]);
-        const unsigned* r2 = reinterpret_cast<const unsigned*>(&vst[i][2]);
-        const unsigned* r3 = reinterpret_cast<const unsigned*>(&vst[i][3]);
-        uint4 outv[4];
-        unsigned* ow = reinterpret_cast<unsigned*>(outv);
+        // 4 keys x 8 channels -> 8 channels x 4 keys: piece w holds channels 2w, 2w+1
+        u32x4 outv[4];
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
-          ow[4 * w + 0] = __builtin_amdgcn_perm(r1[w], r0[w], 0x05040100u);  // d=2w  : keys 0,1
-          ow[4 * w + 1] = __builtin_amdgcn_perm(r3[w], r2[w], 0x05040100u);  // d=2w  : keys 2,3
-          ow[4 * w + 2] = __builtin_amdgcn_perm(r1[w], r0[w], 0x07060302u);  // d=2w+1: keys 0,1
-          ow[4 * w + 3] = __builtin_amdgcn_perm(r3[w], r2[w], 0x07060302u);  // d=2w+1: keys 2,3
+          outv[w][0] = __builtin_amdgcn_perm(vst[i][1][w], vst[i][0][w], 0x05040100u);  // d=2w  : keys 0,1
+          outv[w][1] = __builtin_amdgcn_perm(vst[i][3][w], vst[i][2][w], 0x05040100u);  // d=2w  : keys 2,3
+          outv[w][2] = __builtin_amdgcn_perm(vst[i][1][w], vst[i][0][w], 0x07060302u);  // d=2w+1: keys 0,1
+          outv[w][3] = __builtin_amdgcn_perm(vst[i][3][w], vst[i][2][w], 0x07060302u);  // d=2w+1: keys 2,3
         }
-        uint4* dst = reinterpret_cast<uint4*>(vb + ((size_t)kg * D + c * 8) * 8);
+        // the four 16-byte pieces of this thread's 64-byte segment go to slots
+        // w ^ ((c >> 1) & 3): 8 consecutive lanes then cover all banks once
+        unsigned char* dst = vb + kg * V_ROW + c * 64;
+        const int sw = (c >> 1) & 3;
 #pragma unroll
-        for (int w = 0; w < 4; ++w) dst[w] = outv[w];
+        for (int w = 0; w < 4; ++w) *reinterpret_cast<u32x4*>(dst + ((w ^ sw) << 4)) = outv[w];
       }
     }
     if (MODE == kProfile && tid < BN) {
@@ -253,6 +269,14 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
 
   int buf = 0;
   const int swz = k_swizzle<D>(r);   // tile rows kb*32 + r: swizzle depends on r only
+  // byte offset of channel d = 32 db + r inside a V^T key-group row (see store_tile)
+  int v_off[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db) {
+    const int d = db * 32 + r;
+    const int c = d >> 3, w = (d >> 1) & 3;
+    v_off[db] = c * 64 + ((w ^ ((c >> 1) & 3)) << 4) + (d & 1) * 8;
+  }
   for (int j = j0; j < j1; ++j) {
     const int col = MODE == kSparse ? cols[j] : j;
     const bool has_next = j + 1 < j1;
@@ -285,8 +309,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          const int4 code = *reinterpret_cast<const int4*>(&key_code[buf * BN + kb * 32 + 8 * i + 4 * g]);
-          const int cc[4] = {code.x, code.y, code.z, code.w};
+          const i32x4 cc = *reinterpret_cast<const i32x4*>(&key_code[buf * BN + kb * 32 + 8 * i + 4 * g]);
 #pragma unroll
           for (int jj = 0; jj < 4; ++jj) {
             const bool keep = ((unsigned)(cc[jj] - win_lo) <= win_span) || cc[jj] == kCodeKeep;
@@ -309,11 +332,23 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
       for (int e = 0; e < 16; ++e) m_loc = fmaxf(m_loc, sacc[kb][e]);
-    m_loc = fmaxf(m_loc, other_half(m_loc));
-    const float m_new = fmaxf(m_run, m_loc);
-    const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * a.scale_log2);
-    m_run = m_new;
-    const float mc = m_new * a.scale_log2;
+    m_loc = both_halves_max(m_loc);
+    // The running maximum is only raised when some row's tile maximum exceeds it by
+    // more than 2^kLazyLog2 after scaling; until then the exponentials are taken
+    // against the older (smaller) reference and may reach 2^kLazyLog2, which fp32
+    // sums and bf16 weights hold without loss.  The result is mathematically the
+    // same softmax; the O^T and row-sum rescale is skipped on most tiles.
+    if (__builtin_amdgcn_ballot_w64(m_loc > m_run + a.lazy_tau) != 0) {
+      const float m_new = fmaxf(m_run, m_loc);
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * a.scale_log2);
+      m_run = m_new;
+      l_run *= alpha;
+#pragma unroll
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
+    }
+    const float mc = m_run * a.scale_log2;
     float l_loc = 0.f;
     bf16x8 pb[KB][2];
 #pragma unroll
@@ -328,11 +363,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
         }
         pb[kb][kk] = __builtin_convertvector(p, bf16x8);
       }
-    l_run = l_run * alpha + l_loc;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
+    l_run += l_loc;
 
     // ---- O^T += V^T P^T
 #pragma unroll
@@ -342,9 +373,9 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
         const int kg = kb * 8 + kk * 4 + g;
 #pragma unroll
         for (int db = 0; db < DB; ++db) {
-          const unsigned char* vp = vbuf + ((size_t)kg * D + db * 32 + r) * 8;
+          const unsigned char* vp = vbuf + kg * V_ROW + v_off[db];
           const bf16x4 lo = *reinterpret_cast<const bf16x4*>(vp);
-          const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vp + 2 * D * 8);
+          const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vp + 2 * V_ROW);
           const bf16x8 va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
           oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[kb][kk], oacc[db], 0, 0, 0);
         }
@@ -356,7 +387,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   }
 
   // ---- epilogue: normalise and store.  oacc[db][4 i + jj] = O[query r][32 db + 8 i + 4 g + jj]
-  const float l_tot = l_run + other_half(l_run);
+  const float l_tot = both_halves_sum(l_run);
   const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
   if (MODE == kProfile) {
     if (qslot < a.t) {
@@ -448,6 +479,7 @@ AttnArgs base_args(const Geo& g, const void* q, const void* k, const void* v, vo
   a.o = o;
   a.N = g.N; a.nk = g.nk; a.BH = g.B * g.H;
   a.scale_log2 = g.scale * 1.4426950408889634f;
+  a.lazy_tau = kLazyLog2 / a.scale_log2;
   a.off = g.off; a.video_end = g.video_end; a.F = g.F; a.P = g.P;
   a.w_s = g.w_s; a.w_t = g.w_t; a.sink = g.sink;
   return a;
