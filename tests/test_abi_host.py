@@ -1,0 +1,170 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header
+declares, validates arguments before touching the GPU, and its host tile-list
+builder matches the oracle bit-exactly."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2502_01776_amd as S
+from paper_2502_01776_amd import binding
+from oracle import svg_oracle as O
+from workloads import get_config
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "svg.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(svg_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = header_functions()
+    assert "svg_profile_heads" in names and "svg_sparse_attn_fwd" in names and len(names) >= 10
+    lib = S.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_binding_has_same_names_as_header():
+    for n in header_functions():
+        assert hasattr(S, n) or n == "svg_last_hip_error", n
+
+
+def test_shape_struct_matches_header_layout():
+    assert C.sizeof(S.SvgShape) == 13 * 4
+    assert [f[0] for f in S.SvgShape._fields_] == [
+        "B", "H", "F", "P", "T", "D", "text_first", "w_s", "w_t", "sink_first_frame",
+        "block_m", "block_n", "softmax_scale"]
+
+
+def test_strerror_and_version():
+    assert S.svg_strerror(0) == "ok"
+    for code in (-1, -2, -3, -4, -5, -99):
+        assert isinstance(S.svg_strerror(code), str) and S.svg_strerror(code)
+    assert re.match(r"^\d+\.\d+$", S.svg_version())
+
+
+CASES = ["tiny", "mid64", "mid128", "cogvideox_v1"]
+
+
+@pytest.mark.parametrize("name", CASES)
+@pytest.mark.parametrize("pattern", [0, 1])
+@pytest.mark.parametrize("sink", [0, 1])
+def test_host_tile_list_is_bit_exact(name, pattern, sink):
+    if name == "cogvideox_v1" and sink:
+        pytest.skip("covered by the smaller shapes")
+    cfg = get_config(name, sink_first_frame=sink)
+    rp, ci = S.svg_tile_list_build(S.shape_from_config(cfg), pattern)
+    g = O.Geometry.from_config(cfg)
+    orp, oci = O.tile_list(g, pattern)
+    assert rp.dtype == np.int32 and ci.dtype == np.int32
+    assert np.array_equal(rp, orp) and np.array_equal(ci, oci)
+
+
+@pytest.mark.parametrize("name", ["wan21_14b", "cogvideox_v15", "hunyuan", "hunyuan_skip85", "hunyuan_keep31"])
+def test_host_tile_list_sampled_rows_at_full_size(name):
+    cfg = get_config(name)
+    sh, g = S.shape_from_config(cfg), O.Geometry.from_config(cfg)
+    nq, nk = S.svg_tile_counts(sh)
+    assert (nq, nk) == O.n_tiles(g)
+    for pattern in (0, 1):
+        rp, ci = S.svg_tile_list_build(sh, pattern)
+        assert rp[0] == 0 and rp[-1] == len(ci) and (np.diff(rp) > 0).all()
+        for a in (0, 1, nq // 3, nq // 2, nq - 2, nq - 1):
+            assert np.array_equal(ci[rp[a]:rp[a + 1]], O.kept_tiles_of_row(g, pattern, a)), (pattern, a)
+
+
+def test_tile_list_geometry_variants():
+    base = dict(get_config("mid64"), B=1, H=1)
+    for F, P, T, tf, ws, wt, bm, bn in [(1, 200, 0, 1, 0, 3, 128, 64), (9, 1, 3, 0, 2, 0, 32, 32),
+                                        (2, 5, 0, 1, 1, 1, 128, 64), (3, 64, 64, 0, 0, 0, 32, 32),
+                                        (6, 70, 9, 1, 5, 69, 128, 64), (5, 100, 130, 0, 1, 7, 32, 32)]:
+        for sink in (0, 1):
+            cfg = dict(base, F=F, P=P, T=T, text_first=tf, w_s=ws, w_t=wt, block_m=bm, block_n=bn,
+                       sink_first_frame=sink)
+            sh, g = S.shape_from_config(cfg), O.Geometry.from_config(cfg)
+            for pattern in (0, 1):
+                rp, ci = S.svg_tile_list_build(sh, pattern)
+                orp, oci = O.tile_list(g, pattern)
+                assert np.array_equal(rp, orp) and np.array_equal(ci, oci), (cfg, pattern)
+
+
+def test_tile_list_capacity_and_size_query():
+    sh = S.shape_from_config(get_config("mid64"))
+    nq, _ = S.svg_tile_counts(sh)
+    rp = np.zeros(nq + 1, np.int32)
+    nnz = C.c_int64()
+    lib = S.lib()
+    assert lib.svg_tile_list_build(C.byref(sh), 0, rp.ctypes.data, None, 0, C.byref(nnz)) == 0
+    assert nnz.value == rp[-1] > 0
+    small = np.zeros(3, np.int32)
+    assert lib.svg_tile_list_build(C.byref(sh), 0, rp.ctypes.data, small.ctypes.data, 3, C.byref(nnz)) == -1
+    assert nnz.value == rp[-1]
+    assert lib.svg_tile_list_build(C.byref(sh), 2, rp.ctypes.data, None, 0, C.byref(nnz)) == -1
+    assert lib.svg_tile_list_build(C.byref(sh), 0, None, None, 0, C.byref(nnz)) == -1
+
+
+def _bad_shapes():
+    good = get_config("mid64")
+    yield dict(good, D=96), -2
+    yield dict(good, block_m=64, block_n=64), -2
+    yield dict(good, B=0), -1
+    yield dict(good, F=0), -1
+    yield dict(good, T=-1), -1
+    yield dict(good, w_s=-1), -1
+    yield dict(good, text_first=2), -1
+    yield dict(good, F=4096, P=4096), -2       # N beyond the supported range
+
+
+def test_invalid_shapes_are_rejected_before_any_launch():
+    lib = S.lib()
+    a = 0x1000   # never dereferenced: the shape is checked first
+    for cfg, code in _bad_shapes():
+        sh = S.shape_from_config(cfg)
+        assert S.svg_workspace_bytes(sh, 16) == 0
+        assert lib.svg_layout_fwd(C.byref(sh), a, a + 0x100000000, None, None) == code
+        assert lib.svg_dense_attn_fwd(C.byref(sh), a, a, a, a, None, 0, None) == code
+        assert lib.svg_profile_heads(C.byref(sh), a, a, a, a, 4, a, None, a, 1 << 40, None) == code
+        with pytest.raises(S.SvgError):
+            S.svg_tile_counts(sh)
+
+
+def test_pointer_checks_without_gpu():
+    lib = S.lib()
+    sh = S.shape_from_config(get_config("mid64"))
+    nbytes = sh.B * sh.H * sh.N * sh.D * 2
+    a, b = 0x10000000, 0x10000000 + 4 * nbytes
+    # NULL and misaligned tensors
+    assert lib.svg_layout_fwd(C.byref(sh), None, b, None, None) == -1
+    assert lib.svg_layout_fwd(C.byref(sh), a + 2, b, None, None) == -1
+    assert lib.svg_dense_attn_fwd(C.byref(sh), a, a, None, b, None, 0, None) == -1
+    assert lib.svg_sparse_attn_fwd(C.byref(sh), a, a, a, b, None, None, None, None, None, None, 0, None) == -1
+    assert lib.svg_sparse_attn_fwd(C.byref(sh), a, a, a, b, a, a, a, None, None, None, 0, None) == -1
+    # aliasing
+    assert lib.svg_layout_fwd(C.byref(sh), a, a, None, None) == -4
+    assert lib.svg_layout_inv(C.byref(sh), a, a + nbytes - 16, None, None) == -4
+    assert lib.svg_dense_attn_fwd(C.byref(sh), a, a, a, a, None, 0, None) == -4
+    # workspace
+    need = S.svg_workspace_bytes(sh, 24)
+    assert need == 3 * sh.B * sh.H * 24 * sh.D * 4
+    assert lib.svg_profile_heads(C.byref(sh), a, a, a, a, 24, a, None, None, 0, None) == -3
+    assert lib.svg_profile_heads(C.byref(sh), a, a, a, a, 24, a, None, b, need - 1, None) == -3
+    assert lib.svg_profile_heads(C.byref(sh), a, a, a, a, 0, a, None, b, need, None) == -1
+    assert lib.svg_profile_heads(C.byref(sh), a, a, a, None, 24, a, None, b, need, None) == -1
+
+
+def test_product_package_does_not_import_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2502_01776_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".cpp", ".hip", ".h")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert "oracle" not in text, f
+    otext = open(os.path.join(ROOT, "oracle", "svg_oracle.py")).read()
+    assert "paper_2502_01776_amd" not in otext and "workloads" not in otext

@@ -1,0 +1,99 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times:
+the whole layer is run once on the GPU; the oracle then recomputes sampled outputs
+(query tiles of several heads of each label, sampled profiled heads, whole heads
+of the layout transform)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2502_01776_amd as S
+from oracle import svg_oracle as O
+from workloads import get_config, make_qkv, sample_rows, planted_labels
+from helpers import f64, bits, dev_i32, device_tile_lists, gpu_profile, assert_attn_close, labels_match
+
+pytestmark = pytest.mark.gpu
+
+
+def run_layer(cfg):
+    sh = S.shape_from_config(cfg)
+    q, k, v = make_qkv(cfg, device="cuda")
+    rows = sample_rows(cfg)
+    labels, mse = gpu_profile(sh, q, k, v, rows)
+    lists = device_tile_lists(sh)
+    qp, kp, vp, op, o = (torch.empty_like(q) for _ in range(5))
+    S.svg_layout_fwd(sh, q, qp, labels)
+    S.svg_layout_fwd(sh, k, kp, labels)
+    S.svg_layout_fwd(sh, v, vp, labels)
+    S.svg_sparse_attn_fwd(sh, qp, kp, vp, op, labels, *lists)
+    S.svg_layout_inv(sh, op, o, labels)
+    torch.cuda.synchronize()
+    return sh, (q, k, v), rows, labels, mse, (qp, kp, vp, op), o
+
+
+@pytest.mark.parametrize("name", ["cogvideox_v1", "hunyuan_skip85"])
+def test_full_size_layer_sampled(name):
+    cfg = get_config(name)
+    g = O.Geometry.from_config(cfg)
+    sh, (q, k, v), rows, labels, mse, (qp, kp, vp, op), o = run_layer(cfg)
+    lab = labels.cpu().numpy()
+    assert np.array_equal(lab, planted_labels(cfg)), "profiled labels differ from the planted ones"
+    nq, nk = O.n_tiles(g)
+
+    # profiling: two heads (one of each label) recomputed by the oracle on a subset of rows
+    sub = rows[:: max(1, len(rows) // 96)]
+    for h in (0, 1):
+        g1 = O.Geometry(**{**g.__dict__, "B": 1, "H": 1})
+        omse, olab = O.profile_heads(f64(q[0, h])[None, None], f64(k[0, h])[None, None],
+                                     f64(v[0, h])[None, None], sub, g1)
+        l1, m1 = gpu_profile(S.shape_from_config(cfg, B=1, H=1), q[0, h].contiguous(), k[0, h].contiguous(),
+                             v[0, h].contiguous(), sub)
+        assert labels_match(l1, omse, olab)
+        assert np.allclose(m1.cpu().numpy().reshape(1, 1, 2), omse, rtol=0.05, atol=2e-5)
+        assert int(l1[0]) == int(lab[h])
+
+    # layout: head 1 (temporal) bit-exact, head 0 (spatial) untouched
+    assert np.array_equal(bits(qp[0, 1]), O.layout_fwd(bits(q[0, 1]), g))
+    assert np.array_equal(bits(vp[0, 0]), bits(v[0, 0]))
+    assert np.array_equal(bits(o[0, 1]), O.layout_inv(bits(op[0, 1]), g))
+
+    # block-sparse attention on sampled query tiles: first, second, frame-straddling,
+    # middle, last full, ragged last
+    tiles = sorted({0, 1, (g.off + g.P) // g.block_m, nq // 2, nq - 2, nq - 1})
+    for h in (0, 1, g.H - 2, g.H - 1):
+        pat = int(lab[h])
+        rp = np.zeros(nq + 1, dtype=np.int64)
+        cols = []
+        for a in range(nq):
+            c = O.kept_tiles_of_row(g, pat, a) if a in tiles else np.zeros(0, np.int32)
+            cols.append(c)
+            rp[a + 1] = rp[a] + len(c)
+        ci = np.concatenate(cols)
+        # the oracle works in the order the tile list refers to
+        qh, kh, vh = f64(q[0, h]), f64(k[0, h]), f64(v[0, h])
+        if pat == O.TEMPORAL:
+            qh, kh, vh = O.layout_fwd(qh, g), O.layout_fwd(kh, g), O.layout_fwd(vh, g)
+        ref = O.sparse_attention_head(qh, kh, vh, rp, ci, g, q_tiles=tiles)
+        got = op[0, h]
+        for a in tiles:
+            r0, r1 = a * g.block_m, min(g.N, (a + 1) * g.block_m)
+            assert_attn_close(got[r0:r1], ref[r0:r1], f"{name} head {h} tile {a}")
+        # and the final output is that result permuted back
+        if pat == O.TEMPORAL:
+            perm = O.layout_perm(g)
+            assert np.array_equal(bits(o[0, h]), bits(op[0, h])[perm])
+        else:
+            assert np.array_equal(bits(o[0, h]), bits(op[0, h]))
+
+
+def test_full_size_dense_sampled_rows():
+    cfg = get_config("cogvideox_v1")
+    g = O.Geometry.from_config(cfg)
+    sh = S.shape_from_config(cfg)
+    q, k, v = make_qkv(cfg, device="cuda")
+    o = torch.empty_like(q)
+    S.svg_dense_attn_fwd(sh, q, k, v, o)
+    torch.cuda.synchronize()
+    rows = np.array([0, 1, 127, 128, 225, 226, 5000, 17775 - 128, 17775])
+    for h in (0, 47):
+        ref = O.dense_attention_head(f64(q[0, h]), f64(k[0, h]), f64(v[0, h]), g, rows=rows)
+        assert_attn_close(o[0, h][rows], ref, f"dense head {h}")
