@@ -45,7 +45,7 @@ enum Mode { kDense = 0, kSparse = 1, kProfile = 2 };
 constexpr int kCodeDrop = 0x7fffffff;   // key beyond N: never kept
 constexpr int kCodeKeep = 0x7ffffffe;   // text key / sink key: kept by every query
 constexpr float kNegBig = -1.0e30f;     // finite stand-in for -inf as the initial row maximum
-constexpr float kLazyLog2 = 8.0f;       // exponentials may reach 2^8 before the maximum is raised
+constexpr float kLazySum = 8192.0f;      // a lane's per-tile sum of exponentials above this forces a new reference maximum
 
 struct AttnArgs {
   const __bf16* q;
@@ -57,12 +57,11 @@ struct AttnArgs {
   const int32_t* col_idx[2];
   const int32_t* rows;        // profile: sampled rows
   int t;                      // profile: number of sampled rows
-  int N, nk, BH;
-  int nqt;                    // query tiles per head (profile: ceil(t/BM))
+  int N, nq, nk, BH;
+  int nqt;                    // row groups (workgroups) per head: ceil(nq / tiles per workgroup); profile: ceil(t / rows per workgroup)
   int reverse_q;              // process query tiles last-to-first (heavy text-suffix tiles first)
   int total;                  // logical workgroups
   float scale_log2;           // softmax scale * log2(e)
-  float lazy_tau;             // raw-logit margin below which the running maximum is not raised
   int off, video_end, F, P, w_s, w_t, sink;
 };
 
@@ -87,46 +86,58 @@ __device__ __forceinline__ float both_halves_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int D, int NW, int BN, int MODE>
-__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs a) {
-  constexpr int BM = 32 * NW;
+template <int D, int NW, int QB, int BN, int MODE>
+__global__ __launch_bounds__(64 * NW, (NW == 4 && QB == 1) ? 2 : 1) void attn_kernel(AttnArgs a) {
+  constexpr int BMW = 32 * QB * NW;      // query rows per workgroup
+  constexpr int TILE_M = 32 * NW;        // query-tile rows of the tile list (block_m)
+  constexpr int QT = BMW / TILE_M;       // query tiles per workgroup (= QB)
   constexpr int THREADS = 64 * NW;
   constexpr int CPR = D / 8;             // 16-byte pieces per row
   constexpr int KB = BN / 32;            // 32-key blocks per tile
   constexpr int DS = D / 16;             // k-steps of the first product
   constexpr int DB = D / 32;             // 32-row blocks of O^T
   constexpr int K_PIECES = BN * CPR;
-  constexpr int K_PER_THREAD = K_PIECES / THREADS;
-  constexpr int V_UNITS = (BN / 4) * CPR;   // a unit = 4 keys x 8 channels
-  constexpr int V_PER_THREAD = (V_UNITS + THREADS - 1) / THREADS;
+  constexpr int V_UNITS = (BN / 8) * CPR;   // a unit = 8 keys x 8 channels
+  // Staging work split: with 4 wavefronts the first V_UNITS threads stage V (8 row
+  // loads + register transpose each) and the others stage K; a single wavefront
+  // does both.
+  constexpr bool SPLIT = NW == 4;
+  constexpr int K_THREADS = SPLIT ? THREADS - V_UNITS : THREADS;
+  constexpr int K_PER_THREAD = (K_PIECES + K_THREADS - 1) / K_THREADS;
+  constexpr int V_PER_THREAD = SPLIT ? 1 : (V_UNITS + THREADS - 1) / THREADS;
   constexpr int K_BYTES = BN * D * 2;
-  // V^T staging: [key/4][d][4 keys] with each key-group row padded by 128 bytes, so
-  // that the two half-waves of a ds_read_b64 (key groups kg and kg+1) fall on
-  // different banks.
-  constexpr int V_ROW = D * 8 + 128;
-  constexpr int V_BYTES = (BN / 4) * V_ROW;
+  // V^T staging: [8-key group][d][8 keys], 16 bytes per (group, d): one ds_read_b128
+  // is a whole A operand of the second product.  Group (kb, kk, g) holds the keys
+  // 32 kb + 16 kk + 4 g + {0..3, 8..11}, i.e. the k-slots of half-wave g.  Inside a
+  // group the 16-byte slot of channel d = 8 c + dd is 8 c + (dd ^ (c & 7)), which
+  // makes both the transposing writes and the operand reads conflict-free.
+  constexpr int V_ROW = D * 16;
+  constexpr int V_BYTES = (BN / 8) * V_ROW;
   constexpr int STAGE_BYTES = K_BYTES + V_BYTES;
-  static_assert(K_PIECES % THREADS == 0, "K tile must split evenly over the workgroup");
+  constexpr int kNoTile = 0x7fffffff;
+  static_assert(!SPLIT || V_UNITS < THREADS, "no threads left to stage K");
+  static_assert(!SPLIT || K_THREADS % CPR == 0, "K staging threads must cover whole rows");
+  static_assert(QT == QB, "a wavefront's rows must lie in one query tile");
 
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE_BYTES];
   __shared__ __attribute__((aligned(16))) int key_code[MODE == kProfile ? 2 * BN : 4];
 
-  // ---- which (head, query tile) is this workgroup?  Consecutive logical ids are
+  // ---- which (head, row group) is this workgroup?  Consecutive logical ids are
   // placed on the same XCD (workgroups are dealt round-robin over the 8 XCDs), so
   // the query tiles that stream the same K/V share one L2.
   const int per_xcd = (a.total + 7) >> 3;
   const int lid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
   if (lid >= a.total) return;
-  int bh, qt, variant = 0;
+  int bh, grp, variant = 0;
   if (MODE == kProfile) {
     bh = lid / (3 * a.nqt);
     const int rem = lid - bh * 3 * a.nqt;
     variant = rem / a.nqt;
-    qt = rem - variant * a.nqt;
+    grp = rem - variant * a.nqt;
   } else {
     bh = lid / a.nqt;
-    qt = lid - bh * a.nqt;
-    if (a.reverse_q) qt = a.nqt - 1 - qt;
+    grp = lid - bh * a.nqt;
+    if (a.reverse_q) grp = a.nqt - 1 - grp;
   }
 
   const int tid = threadIdx.x;
@@ -134,114 +145,210 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   const int wave = tid >> 6;
   const int g = lane >> 5;       // which half of the wavefront
   const int r = lane & 31;       // query column within the wave / row of the A operand
+  const int my_sub = (wave * 32 * QB) / TILE_M;   // which of the workgroup's query tiles this wave is in
 
   const size_t head = (size_t)bh * a.N;
   const __bf16* kh = a.k + head * D;
   const __bf16* vh = a.v + head * D;
 
-  // ---- tile range
-  int j0 = 0, j1 = a.nk;
+  // ---- kept-tile lists of the workgroup's query tiles (sparse) or the full range
   const int32_t* cols = nullptr;
+  int li[QT], le[QT];            // cursor and end of each query tile's list
+  int jdense = 0;
   if (MODE == kSparse) {
     const int pat = a.labels ? (a.labels[bh] != 0) : 0;
     const int32_t* rp = a.row_ptr[pat];
     cols = a.col_idx[pat];
-    j0 = rp[qt];
-    j1 = rp[qt + 1];
+#pragma unroll
+    for (int s = 0; s < QT; ++s) {
+      const int qt = grp * QT + s;
+      li[s] = qt < a.nq ? rp[qt] : 0;
+      le[s] = qt < a.nq ? rp[qt + 1] : 0;
+    }
+  }
+  // smallest key tile any of the lists still holds (they ascend), or kNoTile
+  auto peek = [&]() -> int {
+    if (MODE != kSparse) return jdense < a.nk ? jdense : kNoTile;
+    int c = kNoTile;
+#pragma unroll
+    for (int s = 0; s < QT; ++s)
+      if (li[s] < le[s]) c = min(c, cols[li[s]]);
+    return c;
+  };
+  // consume `col` from every list whose head it is; returns whether this wave's tile keeps it
+  auto take = [&](int col) -> bool {
+    if (MODE != kSparse) {
+      ++jdense;
+      return true;
+    }
+    bool mine = false;
+#pragma unroll
+    for (int s = 0; s < QT; ++s) {
+      const bool use = li[s] < le[s] && cols[li[s]] == col;
+      li[s] += use ? 1 : 0;
+      if (s == my_sub) mine = use;
+    }
+    return mine;
+  };
+
+  // ---- this lane's query rows (one per 32-query block)
+  int qslot[QB], qrow[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    qslot[qb] = grp * BMW + wave * 32 * QB + qb * 32 + r;   // row (profile: index into rows[])
+    if (MODE == kProfile) qrow[qb] = a.rows[min(qslot[qb], a.t - 1)];
+    else qrow[qb] = min(qslot[qb], a.N - 1);
   }
 
-  // ---- this lane's query row
-  const int qslot = qt * BM + wave * 32 + r;        // row of the tile (profile: index into rows[])
-  int qrow;
-  if (MODE == kProfile) qrow = a.rows[min(qslot, a.t - 1)];
-  else qrow = min(qslot, a.N - 1);
-
   // profile: window test  (unsigned)(code - lo) <= span  ||  code == kCodeKeep
-  int win_lo = 0;
-  unsigned win_span = 0x7ffffffeu;
-  if (MODE == kProfile && variant != 0) {
-    const bool text_q = qrow < a.off || qrow >= a.video_end;
-    if (!text_q) {
-      const int vq = qrow - a.off;
-      const int fq = vq / a.P;
-      const int c = variant == 1 ? fq : vq - fq * a.P;
-      const int w = variant == 1 ? a.w_s : a.w_t;
-      win_lo = c - w;
-      win_span = 2u * (unsigned)w;
+  int win_lo[QB];
+  unsigned win_span[QB];
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb) {
+    win_lo[qb] = 0;
+    win_span[qb] = 0x7ffffffeu;
+    if (MODE == kProfile && variant != 0) {
+      const bool text_q = qrow[qb] < a.off || qrow[qb] >= a.video_end;
+      if (!text_q) {
+        const int vq = qrow[qb] - a.off;
+        const int fq = vq / a.P;
+        const int c = variant == 1 ? fq : vq - fq * a.P;
+        const int w = variant == 1 ? a.w_s : a.w_t;
+        win_lo[qb] = c - w;
+        win_span[qb] = 2u * (unsigned)w;
+      }
     }
   }
 
   // ---- Q^T as the B operand: lane (g, r) holds Q[qrow][16 s + 8 g .. +8]
-  bf16x8 qreg[DS];
-  {
-    const __bf16* qp = a.q + (head + qrow) * D + g * 8;
+  bf16x8 qreg[QB][DS];
 #pragma unroll
-    for (int s = 0; s < DS; ++s) qreg[s] = *reinterpret_cast<const bf16x8*>(qp + s * 16);
+  for (int qb = 0; qb < QB; ++qb) {
+    const __bf16* qp = a.q + (head + qrow[qb]) * D + g * 8;
+#pragma unroll
+    for (int s = 0; s < DS; ++s) qreg[qb][s] = *reinterpret_cast<const bf16x8*>(qp + s * 16);
   }
 
-  f32x16 oacc[DB];
+  f32x16 oacc[QB][DB];
+  float m_run[QB], l_run[QB];   // running row maximum (raw logits) and this lane's share of the row sum
 #pragma unroll
-  for (int db = 0; db < DB; ++db)
+  for (int qb = 0; qb < QB; ++qb) {
+    m_run[qb] = kNegBig;
+    l_run[qb] = 0.f;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
-  float m_run = kNegBig;   // running row maximum (raw logits, before scaling)
-  float l_run = 0.f;       // this lane's share of the running row sum
+    for (int db = 0; db < DB; ++db)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) oacc[qb][db][e] = 0.f;
+  }
 
-  u32x4 kst[K_PER_THREAD];
-  u32x4 vst[V_PER_THREAD][4];
+  constexpr int STAGE_REGS = SPLIT ? (K_PER_THREAD > 8 ? K_PER_THREAD : 8) : 1;
+  u32x4 stg[STAGE_REGS];                 // split roles: K pieces or the 8 rows of a V unit
+  u32x4 kst[SPLIT ? 1 : K_PER_THREAD];   // single wavefront: both
+  u32x4 vst[SPLIT ? 1 : V_PER_THREAD][8];
+  // staging role per wavefront (V_UNITS is a multiple of 64): read through
+  // readfirstlane so that the compiler treats the role branch as scalar
+  static_assert(!SPLIT || V_UNITS % 64 == 0, "V staging must be done by whole wavefronts");
+  const bool v_role = SPLIT && __builtin_amdgcn_readfirstlane(tid >> 6) < V_UNITS / 64;
 
-  auto load_tile = [&](int col) {
-    const int key0 = col * BN;
+  // row of the e-th key of V group kg8 = (kb, kk, g):  32 kb + 16 kk + 4 g + e (+4 if e >= 4)
+  auto v_key = [](int kg8, int e) { return (kg8 >> 1) * 16 + (kg8 & 1) * 4 + e + (e >= 4 ? 4 : 0); };
+
+  // Global -> register staging uses raw buffer loads: the descriptor of a tile starts
+  // at the tile's first key row and covers the rows up to N, so the per-thread
+  // offsets are loop invariant, no clamping arithmetic is needed, and rows beyond N
+  // (ragged last tile) read as zero.
+  constexpr unsigned kRsrcFlags = 0x00020000u;   // raw buffer, 32-bit data format (gfx9 encoding)
+  int stage_off[SPLIT ? 1 : (K_PER_THREAD > V_PER_THREAD ? K_PER_THREAD : V_PER_THREAD)];
+  if (SPLIT) {
+    if (v_role) stage_off[0] = (v_key(tid / CPR, 0) * D + (tid % CPR) * 8) * 2;
+    else stage_off[0] = (((tid - V_UNITS) / CPR) * D + ((tid - V_UNITS) % CPR) * 8) * 2;
+  }
+  (void)stage_off;
+
+  auto load_tile = [&](int col_any) {
+    // the tile index is the same in every lane; saying so keeps the buffer descriptors in
+    // scalar registers (otherwise each load is wrapped in a loop over distinct descriptors)
+    const int key0 = __builtin_amdgcn_readfirstlane(col_any) * BN;
+    const unsigned bytes_left = (unsigned)(a.N - key0) * (D * 2);
+    const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<__bf16*>(kh + (size_t)key0 * D), 0, bytes_left, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<__bf16*>(vh + (size_t)key0 * D), 0, bytes_left, kRsrcFlags);
+    if (SPLIT) {
+      if (v_role) {
 #pragma unroll
-    for (int i = 0; i < K_PER_THREAD; ++i) {
-      const int u = tid + i * THREADS;
-      const int key = u / CPR, c = u % CPR;
-      const int krow = min(key0 + key, a.N - 1);
-      kst[i] = *reinterpret_cast<const u32x4*>(kh + (size_t)krow * D + c * 8);
-    }
+        for (int e = 0; e < 8; ++e)   // rows 0..3 and 8..11 of the group's first row
+          stg[e] = __builtin_amdgcn_raw_buffer_load_b128(rv, stage_off[0] + (e + (e >= 4 ? 4 : 0)) * (D * 2), 0, 0);
+      } else {
 #pragma unroll
-    for (int i = 0; i < V_PER_THREAD; ++i) {
-      const int u = tid + i * THREADS;
-      if (V_UNITS % THREADS == 0 || u < V_UNITS) {
-        const int kg = u / CPR, c = u % CPR;
-#pragma unroll
-        for (int rr = 0; rr < 4; ++rr) {
-          const int vrow = min(key0 + kg * 4 + rr, a.N - 1);
-          vst[i][rr] = *reinterpret_cast<const u32x4*>(vh + (size_t)vrow * D + c * 8);
+        for (int i = 0; i < K_PER_THREAD; ++i) {
+          // piece u = (tid - V_UNITS) + i*K_THREADS; K_THREADS is a multiple of CPR here
+          if (K_PIECES % K_THREADS == 0 || (tid - V_UNITS) + i * K_THREADS < K_PIECES)
+            stg[i] = __builtin_amdgcn_raw_buffer_load_b128(rk, stage_off[0] + i * (K_THREADS / CPR) * (D * 2), 0, 0);
         }
       }
+    } else {
+#pragma unroll
+      for (int i = 0; i < K_PER_THREAD; ++i) {
+        const int u = tid + i * THREADS;
+        const int key = u / CPR, c = u % CPR;
+        kst[i] = __builtin_amdgcn_raw_buffer_load_b128(rk, (key * D + c * 8) * 2, 0, 0);
+      }
+#pragma unroll
+      for (int i = 0; i < V_PER_THREAD; ++i) {
+        const int u = tid + i * THREADS;
+        if (V_UNITS % THREADS == 0 || u < V_UNITS) {
+          const int kg8 = u / CPR, c = u % CPR;
+#pragma unroll
+          for (int e = 0; e < 8; ++e)
+            vst[i][e] = __builtin_amdgcn_raw_buffer_load_b128(rv, (v_key(kg8, e) * D + c * 8) * 2, 0, 0);
+        }
+      }
+    }
+  };
+
+  // 8 keys x 8 channels (rows[e][w] = channels 2w, 2w+1 of key e) -> LDS as 8 channels x 8 keys
+  auto store_v_unit = [&](unsigned char* vb, int kg8, int c, const u32x4* rows) {
+    unsigned char* dst = vb + kg8 * V_ROW + c * 128;
+    const int sw = c & 7;
+#pragma unroll
+    for (int dd = 0; dd < 8; ++dd) {
+      const unsigned sel = (dd & 1) ? 0x07060302u : 0x05040100u;
+      u32x4 o;
+#pragma unroll
+      for (int kp = 0; kp < 4; ++kp)
+        o[kp] = __builtin_amdgcn_perm(rows[2 * kp + 1][dd >> 1], rows[2 * kp][dd >> 1], sel);
+      *reinterpret_cast<u32x4*>(dst + ((dd ^ sw) << 4)) = o;
     }
   };
 
   auto store_tile = [&](int buf, int col) {
     unsigned char* kb = lds + buf * STAGE_BYTES;
     unsigned char* vb = kb + K_BYTES;
+    if (SPLIT) {
+      if (v_role) {
+        store_v_unit(vb, tid / CPR, tid % CPR, stg);
+      } else {
 #pragma unroll
-    for (int i = 0; i < K_PER_THREAD; ++i) {
-      const int u = tid + i * THREADS;
-      const int key = u / CPR, c = u % CPR;
-      *reinterpret_cast<u32x4*>(kb + key * (D * 2) + ((c ^ k_swizzle<D>(key)) << 4)) = kst[i];
-    }
-#pragma unroll
-    for (int i = 0; i < V_PER_THREAD; ++i) {
-      const int u = tid + i * THREADS;
-      if (V_UNITS % THREADS == 0 || u < V_UNITS) {
-        const int kg = u / CPR, c = u % CPR;
-        // 4 keys x 8 channels -> 8 channels x 4 keys: piece w holds channels 2w, 2w+1
-        u32x4 outv[4];
-#pragma unroll
-        for (int w = 0; w < 4; ++w) {
-          outv[w][0] = __builtin_amdgcn_perm(vst[i][1][w], vst[i][0][w], 0x05040100u);  // d=2w  : keys 0,1
-          outv[w][1] = __builtin_amdgcn_perm(vst[i][3][w], vst[i][2][w], 0x05040100u);  // d=2w  : keys 2,3
-          outv[w][2] = __builtin_amdgcn_perm(vst[i][1][w], vst[i][0][w], 0x07060302u);  // d=2w+1: keys 0,1
-          outv[w][3] = __builtin_amdgcn_perm(vst[i][3][w], vst[i][2][w], 0x07060302u);  // d=2w+1: keys 2,3
+        for (int i = 0; i < K_PER_THREAD; ++i) {
+          const int u = (tid - V_UNITS) + i * K_THREADS;
+          if (K_PIECES % K_THREADS == 0 || u < K_PIECES) {
+            const int key = u / CPR, c = u % CPR;
+            *reinterpret_cast<u32x4*>(kb + key * (D * 2) + ((c ^ k_swizzle<D>(key)) << 4)) = stg[i];
+          }
         }
-        // the four 16-byte pieces of this thread's 64-byte segment go to slots
-        // w ^ ((c >> 1) & 3): 8 consecutive lanes then cover all banks once
-        unsigned char* dst = vb + kg * V_ROW + c * 64;
-        const int sw = (c >> 1) & 3;
+      }
+    } else {
 #pragma unroll
-        for (int w = 0; w < 4; ++w) *reinterpret_cast<u32x4*>(dst + ((w ^ sw) << 4)) = outv[w];
+      for (int i = 0; i < K_PER_THREAD; ++i) {
+        const int u = tid + i * THREADS;
+        const int key = u / CPR, c = u % CPR;
+        *reinterpret_cast<u32x4*>(kb + key * (D * 2) + ((c ^ k_swizzle<D>(key)) << 4)) = kst[i];
+      }
+#pragma unroll
+      for (int i = 0; i < V_PER_THREAD; ++i) {
+        const int u = tid + i * THREADS;
+        if (V_UNITS % THREADS == 0 || u < V_UNITS) store_v_unit(vb, u / CPR, u % CPR, vst[i]);
       }
     }
     if (MODE == kProfile && tid < BN) {
@@ -261,159 +368,209 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     }
   };
 
-  if (j0 < j1) {
-    load_tile(MODE == kSparse ? cols[j0] : j0);
-    store_tile(0, MODE == kSparse ? cols[j0] : j0);
+  // Tile cursor.  One query tile per workgroup (QT == 1): the list is walked with the
+  // entry two tiles ahead already requested, so no scalar load sits between one tile's
+  // barrier and the next tile's global loads.  Several query tiles per workgroup: their
+  // lists are merged on the fly (peek / take).
+  int lj = 0, lcol1 = kNoTile, lcol2 = kNoTile;
+  auto list_at = [&](int j) -> int { return j < le[0] ? cols[j] : kNoTile; };
+  int col;
+  if (MODE == kSparse && QT == 1) {
+    lj = li[0];
+    col = list_at(lj);
+    lcol1 = list_at(lj + 1);
+    lcol2 = list_at(lj + 2);
+  } else {
+    col = peek();
+  }
+  if (col != kNoTile) {
+    load_tile(col);
+    store_tile(0, col);
   }
   __syncthreads();
 
   int buf = 0;
   const int swz = k_swizzle<D>(r);   // tile rows kb*32 + r: swizzle depends on r only
-  // byte offset of channel d = 32 db + r inside a V^T key-group row (see store_tile)
+  // byte offset of channel d = 32 db + r inside a V^T group row (see store_v_unit)
   int v_off[DB];
 #pragma unroll
   for (int db = 0; db < DB; ++db) {
     const int d = db * 32 + r;
-    const int c = d >> 3, w = (d >> 1) & 3;
-    v_off[db] = c * 64 + ((w ^ ((c >> 1) & 3)) << 4) + (d & 1) * 8;
+    const int c = d >> 3, dd = d & 7;
+    v_off[db] = c * 128 + ((dd ^ (c & 7)) << 4);
   }
-  for (int j = j0; j < j1; ++j) {
-    const int col = MODE == kSparse ? cols[j] : j;
-    const bool has_next = j + 1 < j1;
-    int next_col = 0;
-    if (has_next) {
-      next_col = MODE == kSparse ? cols[j + 1] : j + 1;
-      load_tile(next_col);
+  const bool ragged = (a.N % BN) != 0;
+
+  while (col != kNoTile) {
+    bool mine;
+    int next_col;
+    if (MODE == kSparse && QT == 1) {
+      mine = true;
+      next_col = lcol1;
+      lcol1 = lcol2;
+      lcol2 = list_at(lj + 3);
+      ++lj;
+    } else {
+      mine = take(col);
+      next_col = peek();
     }
+    if (next_col != kNoTile) load_tile(next_col);
 
-    const unsigned char* kbuf = lds + buf * STAGE_BYTES;
-    const unsigned char* vbuf = kbuf + K_BYTES;
+    if (mine) {
+      const unsigned char* kbuf = lds + buf * STAGE_BYTES;
+      const unsigned char* vbuf = kbuf + K_BYTES;
 
-    // ---- S^T = K Q^T
-    f32x16 sacc[KB];
+      // ---- S^T = K Q^T : each K operand read from LDS feeds QB products
+      f32x16 sacc[QB][KB];
 #pragma unroll
-    for (int kb = 0; kb < KB; ++kb) {
+      for (int kb = 0; kb < KB; ++kb) {
 #pragma unroll
-      for (int e = 0; e < 16; ++e) sacc[kb][e] = 0.f;
-      const unsigned char* krow = kbuf + (kb * 32 + r) * (D * 2);
+        for (int qb = 0; qb < QB; ++qb)
 #pragma unroll
-      for (int s = 0; s < DS; ++s) {
-        const bf16x8 ka = *reinterpret_cast<const bf16x8*>(krow + (((2 * s + g) ^ swz) << 4));
-        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], sacc[kb], 0, 0, 0);
+          for (int e = 0; e < 16; ++e) sacc[qb][kb][e] = 0.f;
+        const unsigned char* krow = kbuf + (kb * 32 + r) * (D * 2);
+        // keep the operand reads of one 32-key block from being hoisted above the
+        // products of the previous one (bounds the registers held by operands in flight)
+        if (kb > 0) __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int s = 0; s < DS; ++s) {
+          const bf16x8 ka = *reinterpret_cast<const bf16x8*>(krow + (((2 * s + g) ^ swz) << 4));
+#pragma unroll
+          for (int qb = 0; qb < QB; ++qb)
+            sacc[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[qb][s], sacc[qb][kb], 0, 0, 0);
+        }
       }
-    }
 
-    // ---- masking.  sacc[kb][4 i + jj] belongs to key  col*BN + 32 kb + 8 i + 4 g + jj.
-    if (MODE == kProfile) {
+      bf16x8 pb[QB][KB][2];
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        // ---- masking.  sacc[kb][4 i + jj] belongs to key  col*BN + 32 kb + 8 i + 4 g + jj.
+        if (MODE == kProfile) {
+#pragma unroll
+          for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              const i32x4 cc = *reinterpret_cast<const i32x4*>(&key_code[buf * BN + kb * 32 + 8 * i + 4 * g]);
+#pragma unroll
+              for (int jj = 0; jj < 4; ++jj) {
+                const bool keep = ((unsigned)(cc[jj] - win_lo[qb]) <= win_span[qb]) || cc[jj] == kCodeKeep;
+                if (!keep) sacc[qb][kb][4 * i + jj] = -INFINITY;
+              }
+            }
+        } else if (ragged && col == a.nk - 1) {
+          int lim = a.N - col * BN - 4 * g;     // keys with 32 kb + 8 i + jj >= lim are out of range
+          // opaque to the optimiser: keeps this rarely taken masking code inside the
+          // branch instead of being speculated into every tile
+          asm volatile("" : "+v"(lim));
+#pragma unroll
+          for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+              for (int jj = 0; jj < 4; ++jj)
+                if (kb * 32 + 8 * i + jj >= lim) sacc[qb][kb][4 * i + jj] = -INFINITY;
+        }
+
+        // ---- online softmax: one query per lane.
+        // Fast path: exponentials are taken against the current reference m_run without
+        // looking at the tile's maximum.  That is the same softmax as long as nothing
+        // overflows, which the row sum reveals: if any lane's partial sum exceeds
+        // kLazySum (or is inf / NaN) the whole wave takes the slow path, which finds the
+        // tile maximum, raises the reference, rescales O^T and the running sum, and redoes
+        // the tile's exponentials.  With a reference within 2^13 of the true maximum the
+        // fp32 sums and bf16 weights lose nothing, and almost every tile after the first
+        // few stays on the fast path (no max reduction, no rescale).
+        auto exponentiate = [&](float mc) -> float {
+          float l_loc = 0.f;
+#pragma unroll
+          for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int kk = 0; kk < 2; ++kk) {
+              f32x8 p;
+#pragma unroll
+              for (int e = 0; e < 8; ++e) {
+                p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][kb][8 * kk + e], a.scale_log2, -mc));
+                l_loc += p[e];
+              }
+              pb[qb][kb][kk] = __builtin_convertvector(p, bf16x8);
+            }
+          return l_loc;
+        };
+        float l_loc = exponentiate(m_run[qb] * a.scale_log2);
+        if (__builtin_amdgcn_ballot_w64(!(l_loc <= kLazySum)) != 0) {
+          float m_loc = sacc[qb][0][0];
+#pragma unroll
+          for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) m_loc = fmaxf(m_loc, sacc[qb][kb][e]);
+          m_loc = both_halves_max(m_loc);
+          const float m_new = fmaxf(m_run[qb], m_loc);
+          const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * a.scale_log2);
+          m_run[qb] = m_new;
+          l_run[qb] *= alpha;
+#pragma unroll
+          for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) oacc[qb][db][e] *= alpha;
+          l_loc = exponentiate(m_new * a.scale_log2);
+        }
+        l_run[qb] += l_loc;
+      }
+
+      // ---- O^T += V^T P^T : each V^T operand read from LDS feeds QB products
 #pragma unroll
       for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          const i32x4 cc = *reinterpret_cast<const i32x4*>(&key_code[buf * BN + kb * 32 + 8 * i + 4 * g]);
+        for (int kk = 0; kk < 2; ++kk) {
+          const int kg8 = kb * 4 + kk * 2 + g;
+          if (kb + kk > 0) __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int jj = 0; jj < 4; ++jj) {
-            const bool keep = ((unsigned)(cc[jj] - win_lo) <= win_span) || cc[jj] == kCodeKeep;
-            if (!keep) sacc[kb][4 * i + jj] = -INFINITY;
+          for (int db = 0; db < DB; ++db) {
+            const bf16x8 va = *reinterpret_cast<const bf16x8*>(vbuf + kg8 * V_ROW + v_off[db]);
+#pragma unroll
+            for (int qb = 0; qb < QB; ++qb)
+              oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[qb][kb][kk], oacc[qb][db], 0, 0, 0);
           }
         }
-    } else if ((col + 1) * BN > a.N) {
-#pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-#pragma unroll
-          for (int jj = 0; jj < 4; ++jj)
-            if (col * BN + kb * 32 + 8 * i + 4 * g + jj >= a.N) sacc[kb][4 * i + jj] = -INFINITY;
     }
 
-    // ---- online softmax: one query per lane
-    float m_loc = sacc[0][0];
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) m_loc = fmaxf(m_loc, sacc[kb][e]);
-    m_loc = both_halves_max(m_loc);
-    // The running maximum is only raised when some row's tile maximum exceeds it by
-    // more than 2^kLazyLog2 after scaling; until then the exponentials are taken
-    // against the older (smaller) reference and may reach 2^kLazyLog2, which fp32
-    // sums and bf16 weights hold without loss.  The result is mathematically the
-    // same softmax; the O^T and row-sum rescale is skipped on most tiles.
-    if (__builtin_amdgcn_ballot_w64(m_loc > m_run + a.lazy_tau) != 0) {
-      const float m_new = fmaxf(m_run, m_loc);
-      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * a.scale_log2);
-      m_run = m_new;
-      l_run *= alpha;
-#pragma unroll
-      for (int db = 0; db < DB; ++db)
-#pragma unroll
-        for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
-    }
-    const float mc = m_run * a.scale_log2;
-    float l_loc = 0.f;
-    bf16x8 pb[KB][2];
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        f32x8 p;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-          p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][8 * kk + e], a.scale_log2, -mc));
-          l_loc += p[e];
-        }
-        pb[kb][kk] = __builtin_convertvector(p, bf16x8);
-      }
-    l_run += l_loc;
-
-    // ---- O^T += V^T P^T
-#pragma unroll
-    for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-      for (int kk = 0; kk < 2; ++kk) {
-        const int kg = kb * 8 + kk * 4 + g;
-#pragma unroll
-        for (int db = 0; db < DB; ++db) {
-          const unsigned char* vp = vbuf + kg * V_ROW + v_off[db];
-          const bf16x4 lo = *reinterpret_cast<const bf16x4*>(vp);
-          const bf16x4 hi = *reinterpret_cast<const bf16x4*>(vp + 2 * V_ROW);
-          const bf16x8 va = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[kb][kk], oacc[db], 0, 0, 0);
-        }
-      }
-
-    if (has_next) store_tile(buf ^ 1, next_col);
+    if (next_col != kNoTile) store_tile(buf ^ 1, next_col);
     __syncthreads();
     buf ^= 1;
+    col = next_col;
   }
 
   // ---- epilogue: normalise and store.  oacc[db][4 i + jj] = O[query r][32 db + 8 i + 4 g + jj]
-  const float l_tot = both_halves_sum(l_run);
-  const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-  if (MODE == kProfile) {
-    if (qslot < a.t) {
-      float* op = static_cast<float*>(a.o) + (((size_t)variant * a.BH + bh) * a.t + qslot) * D;
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+  for (int qb = 0; qb < QB; ++qb) {
+    const float l_tot = both_halves_sum(l_run[qb]);
+    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+    if (MODE == kProfile) {
+      if (qslot[qb] < a.t) {
+        float* op = static_cast<float*>(a.o) + (((size_t)variant * a.BH + bh) * a.t + qslot[qb]) * D;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          f32x4 x;
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-          for (int jj = 0; jj < 4; ++jj) x[jj] = oacc[db][4 * i + jj] * inv;
-          *reinterpret_cast<f32x4*>(op + db * 32 + 8 * i + 4 * g) = x;
-        }
-    }
-  } else {
-    if (qslot < a.N) {
-      __bf16* op = static_cast<__bf16*>(a.o) + (head + qslot) * D;
+          for (int i = 0; i < 4; ++i) {
+            f32x4 x;
 #pragma unroll
-      for (int db = 0; db < DB; ++db)
+            for (int jj = 0; jj < 4; ++jj) x[jj] = oacc[qb][db][4 * i + jj] * inv;
+            *reinterpret_cast<f32x4*>(op + db * 32 + 8 * i + 4 * g) = x;
+          }
+      }
+    } else {
+      if (qslot[qb] < a.N) {
+        __bf16* op = static_cast<__bf16*>(a.o) + (head + qslot[qb]) * D;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          f32x4 x;
+        for (int db = 0; db < DB; ++db)
 #pragma unroll
-          for (int jj = 0; jj < 4; ++jj) x[jj] = oacc[db][4 * i + jj] * inv;
-          *reinterpret_cast<bf16x4*>(op + db * 32 + 8 * i + 4 * g) = __builtin_convertvector(x, bf16x4);
-        }
+          for (int i = 0; i < 4; ++i) {
+            f32x4 x;
+#pragma unroll
+            for (int jj = 0; jj < 4; ++jj) x[jj] = oacc[qb][db][4 * i + jj] * inv;
+            *reinterpret_cast<bf16x4*>(op + db * 32 + 8 * i + 4 * g) = __builtin_convertvector(x, bf16x4);
+          }
+      }
     }
   }
 }
@@ -455,20 +612,30 @@ __global__ __launch_bounds__(256) void profile_finalize_kernel(const float* ws, 
   }
 }
 
-template <int D, int NW, int BN, int MODE>
-int launch_one(const AttnArgs& a, hipStream_t stream) {
+#ifndef SVG_ATTN_QB
+#define SVG_ATTN_QB 1     // 32-query blocks per wavefront for the 128x64-tile kernels
+#endif
+
+template <int D, int NW, int QB, int BN, int MODE>
+int launch_one(AttnArgs a, int rows_total, hipStream_t stream) {
+  constexpr int BMW = 32 * QB * NW;
+  a.nqt = (rows_total + BMW - 1) / BMW;
+  a.total = (MODE == kProfile ? 3 : 1) * a.BH * a.nqt;
   const unsigned grid = (unsigned)(((a.total + 7) / 8) * 8);
   (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
-  hipLaunchKernelGGL((attn_kernel<D, NW, BN, MODE>), dim3(grid), dim3(64 * NW), 0, stream, a);
+  hipLaunchKernelGGL((attn_kernel<D, NW, QB, BN, MODE>), dim3(grid), dim3(64 * NW), 0, stream, a);
   return hip_status(hipGetLastError());
 }
 
+// rows_total: N for dense / sparse, t for profiling
 template <int MODE>
-int dispatch(const Geo& g, const AttnArgs& a, hipStream_t stream) {
+int dispatch(const Geo& g, const AttnArgs& a, int rows_total, hipStream_t stream) {
   if (g.bm == 128) {
-    return g.D == 128 ? launch_one<128, 4, 64, MODE>(a, stream) : launch_one<64, 4, 64, MODE>(a, stream);
+    return g.D == 128 ? launch_one<128, 4, SVG_ATTN_QB, 64, MODE>(a, rows_total, stream)
+                      : launch_one<64, 4, SVG_ATTN_QB, 64, MODE>(a, rows_total, stream);
   }
-  return g.D == 128 ? launch_one<128, 1, 32, MODE>(a, stream) : launch_one<64, 1, 32, MODE>(a, stream);
+  return g.D == 128 ? launch_one<128, 1, 1, 32, MODE>(a, rows_total, stream)
+                    : launch_one<64, 1, 1, 32, MODE>(a, rows_total, stream);
 }
 
 AttnArgs base_args(const Geo& g, const void* q, const void* k, const void* v, void* o) {
@@ -477,9 +644,8 @@ AttnArgs base_args(const Geo& g, const void* q, const void* k, const void* v, vo
   a.k = static_cast<const __bf16*>(k);
   a.v = static_cast<const __bf16*>(v);
   a.o = o;
-  a.N = g.N; a.nk = g.nk; a.BH = g.B * g.H;
+  a.N = g.N; a.nq = g.nq; a.nk = g.nk; a.BH = g.B * g.H;
   a.scale_log2 = g.scale * 1.4426950408889634f;
-  a.lazy_tau = kLazyLog2 / a.scale_log2;
   a.off = g.off; a.video_end = g.video_end; a.F = g.F; a.P = g.P;
   a.w_s = g.w_s; a.w_t = g.w_t; a.sink = g.sink;
   return a;
@@ -495,11 +661,9 @@ int launch_attention(const Geo& g, const void* q, const void* k, const void* v, 
   a.labels = labels;
   a.row_ptr[0] = row_ptr_s; a.col_idx[0] = col_idx_s;
   a.row_ptr[1] = row_ptr_t; a.col_idx[1] = col_idx_t;
-  a.nqt = g.nq;
-  a.total = a.BH * a.nqt;
   // query tiles holding text rows keep every key tile: start them first
   a.reverse_q = (sparse && g.T > 0 && !g.text_first) ? 1 : 0;
-  return sparse ? dispatch<kSparse>(g, a, stream) : dispatch<kDense>(g, a, stream);
+  return sparse ? dispatch<kSparse>(g, a, g.N, stream) : dispatch<kDense>(g, a, g.N, stream);
 }
 
 int launch_profile(const Geo& g, const void* q, const void* k, const void* v, const int32_t* rows,
@@ -507,9 +671,7 @@ int launch_profile(const Geo& g, const void* q, const void* k, const void* v, co
   AttnArgs a = base_args(g, q, k, v, workspace);
   a.rows = rows;
   a.t = t;
-  a.nqt = (t + g.bm - 1) / g.bm;
-  a.total = 3 * a.BH * a.nqt;
-  int rc = dispatch<kProfile>(g, a, stream);
+  int rc = dispatch<kProfile>(g, a, t, stream);
   if (rc != SVG_OK) return rc;
   (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
   hipLaunchKernelGGL(profile_finalize_kernel, dim3(a.BH), dim3(256), 0, stream, workspace, a.BH, t,
