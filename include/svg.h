@@ -67,7 +67,8 @@ const char* svg_last_hip_error(void);
 const char* svg_version(void);
 
 /* Bytes of device workspace svg_profile_heads needs for `t` sampled rows
- * (three fp32 outputs of shape [B,H,t,D]).  0 if shape is invalid. */
+ * (three fp32 outputs of shape [B,H,t,D] and an int32[t] row order).  0 if shape
+ * is invalid. */
 size_t svg_workspace_bytes(const svg_shape_t* shape, int32_t t);
 
 /* Number of query tiles and key tiles: ceil(N/block_m), ceil(N/block_n). */

@@ -56,6 +56,7 @@ struct AttnArgs {
   const int32_t* row_ptr[2];
   const int32_t* col_idx[2];
   const int32_t* rows;        // profile: sampled rows
+  const int32_t* order_t;     // profile: indices into rows[], grouped by in-frame position (temporal variant)
   int t;                      // profile: number of sampled rows
   int N, nq, nk, BH;
   int nqt;                    // row groups (workgroups) per head: ceil(nq / tiles per workgroup); profile: ceil(t / rows per workgroup)
@@ -87,9 +88,9 @@ __device__ __forceinline__ float both_halves_sum(float x) {
 }
 
 template <int D, int NW, int QB, int BN, int MODE>
-__global__ __launch_bounds__(64 * NW, (NW == 4 && QB == 1) ? 2 : 1) void attn_kernel(AttnArgs a) {
+__global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_kernel(AttnArgs a) {
   constexpr int BMW = 32 * QB * NW;      // query rows per workgroup
-  constexpr int TILE_M = 32 * NW;        // query-tile rows of the tile list (block_m)
+  constexpr int TILE_M = NW >= 4 ? 128 : 32 * NW;   // query-tile rows of the tile list (block_m)
   constexpr int QT = BMW / TILE_M;       // query tiles per workgroup (= QB)
   constexpr int THREADS = 64 * NW;
   constexpr int CPR = D / 8;             // 16-byte pieces per row
@@ -101,7 +102,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && QB == 1) ? 2 : 1) void attn_ke
   // Staging work split: with 4 wavefronts the first V_UNITS threads stage V (8 row
   // loads + register transpose each) and the others stage K; a single wavefront
   // does both.
-  constexpr bool SPLIT = NW == 4;
+  constexpr bool SPLIT = NW >= 4;
   constexpr int K_THREADS = SPLIT ? THREADS - V_UNITS : THREADS;
   constexpr int K_PER_THREAD = (K_PIECES + K_THREADS - 1) / K_THREADS;
   constexpr int V_PER_THREAD = SPLIT ? 1 : (V_UNITS + THREADS - 1) / THREADS;
@@ -117,7 +118,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && QB == 1) ? 2 : 1) void attn_ke
   constexpr int kNoTile = 0x7fffffff;
   static_assert(!SPLIT || V_UNITS < THREADS, "no threads left to stage K");
   static_assert(!SPLIT || K_THREADS % CPR == 0, "K staging threads must cover whole rows");
-  static_assert(QT == QB, "a wavefront's rows must lie in one query tile");
+  static_assert(TILE_M % (32 * QB) == 0, "a wavefront's rows must lie in one query tile");
 
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE_BYTES];
   __shared__ __attribute__((aligned(16))) int key_code[MODE == kProfile ? 2 * BN : 4];
@@ -126,15 +127,22 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && QB == 1) ? 2 : 1) void attn_ke
   // placed on the same XCD (workgroups are dealt round-robin over the 8 XCDs), so
   // the query tiles that stream the same K/V share one L2.
   const int per_xcd = (a.total + 7) >> 3;
-  const int lid = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-  if (lid >= a.total) return;
+  const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
   int bh, grp, variant = 0;
   if (MODE == kProfile) {
-    bh = lid / (3 * a.nqt);
-    const int rem = lid - bh * 3 * a.nqt;
-    variant = rem / a.nqt;
-    grp = rem - variant * a.nqt;
+    // (head, row group) pairs are split into 8 contiguous chunks, one per XCD; inside a
+    // chunk the unmasked passes (every key tile) come first and the two masked passes
+    // (a fraction of the tiles) fill in behind them.  a.total = 3 * BH * nqt.
+    const int pairs = a.BH * a.nqt;
+    const int pairs_per_xcd = (pairs + 7) >> 3;
+    variant = loc / pairs_per_xcd;
+    const int pair = xcd * pairs_per_xcd + (loc - variant * pairs_per_xcd);
+    if (variant > 2 || pair >= pairs) return;
+    bh = pair / a.nqt;
+    grp = pair - bh * a.nqt;
   } else {
+    const int lid = xcd * per_xcd + loc;
+    if (lid >= a.total) return;
     bh = lid / a.nqt;
     grp = lid - bh * a.nqt;
     if (a.reverse_q) grp = a.nqt - 1 - grp;
@@ -166,43 +174,37 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && QB == 1) ? 2 : 1) void attn_ke
       le[s] = qt < a.nq ? rp[qt + 1] : 0;
     }
   }
-  // smallest key tile any of the lists still holds (they ascend), or kNoTile
-  auto peek = [&]() -> int {
-    if (MODE != kSparse) return jdense < a.nk ? jdense : kNoTile;
-    int c = kNoTile;
-#pragma unroll
-    for (int s = 0; s < QT; ++s)
-      if (li[s] < le[s]) c = min(c, cols[li[s]]);
-    return c;
-  };
-  // consume `col` from every list whose head it is; returns whether this wave's tile keeps it
-  auto take = [&](int col) -> bool {
-    if (MODE != kSparse) {
-      ++jdense;
-      return true;
-    }
-    bool mine = false;
-#pragma unroll
-    for (int s = 0; s < QT; ++s) {
-      const bool use = li[s] < le[s] && cols[li[s]] == col;
-      li[s] += use ? 1 : 0;
-      if (s == my_sub) mine = use;
-    }
-    return mine;
-  };
-
   // ---- this lane's query rows (one per 32-query block)
   int qslot[QB], qrow[QB];
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     qslot[qb] = grp * BMW + wave * 32 * QB + qb * 32 + r;   // row (profile: index into rows[])
-    if (MODE == kProfile) qrow[qb] = a.rows[min(qslot[qb], a.t - 1)];
-    else qrow[qb] = min(qslot[qb], a.N - 1);
+    if (MODE == kProfile) {
+      // The temporal variant takes the sampled rows grouped by in-frame position, so
+      // that a workgroup's rows share a narrow position range and most key tiles can be
+      // skipped; results are still written at the row's own slot.
+      int slot = min(qslot[qb], a.t - 1);
+      if (variant == 2) slot = a.order_t[slot];
+      if (qslot[qb] < a.t) qslot[qb] = slot;
+      qrow[qb] = a.rows[slot];
+    } else {
+      qrow[qb] = min(qslot[qb], a.N - 1);
+    }
   }
 
   // profile: window test  (unsigned)(code - lo) <= span  ||  code == kCodeKeep
   int win_lo[QB];
   unsigned win_span[QB];
+  // profile: coordinate range (frames or positions) of the workgroup's rows, for tile skipping
+  __shared__ int wg_range[3];    // min, max, any row that keeps every key
+  if (MODE == kProfile) {
+    if (tid == 0) {
+      wg_range[0] = 0x7fffffff;
+      wg_range[1] = -1;
+      wg_range[2] = variant == 0 ? 1 : 0;
+    }
+    __syncthreads();
+  }
 #pragma unroll
   for (int qb = 0; qb < QB; ++qb) {
     win_lo[qb] = 0;
@@ -216,9 +218,98 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && QB == 1) ? 2 : 1) void attn_ke
         const int w = variant == 1 ? a.w_s : a.w_t;
         win_lo[qb] = c - w;
         win_span[qb] = 2u * (unsigned)w;
+        atomicMin(&wg_range[0], c);
+        atomicMax(&wg_range[1], c);
+      } else {
+        atomicOr(&wg_range[2], 1);
       }
     }
   }
+  // Key intervals that can hold a kept key for ANY row of the workgroup, ascending:
+  // text prefix | frame 0 (sink) | the window around the rows' frames (spatial) or, per
+  // frame, the window around the rows' positions (temporal) | text suffix.  A superset
+  // is enough: the element mask is still applied inside every visited tile.
+  int c_lo = 0, c_hi = -1;
+  bool all_keys = true;
+  if (MODE == kProfile) {
+    __syncthreads();
+    c_lo = wg_range[0];
+    c_hi = wg_range[1];
+    all_keys = wg_range[2] != 0;
+  }
+  int pseg = 0, pj = 0, pjb = -1;
+  auto profile_segment = [&](int sidx, int& k0, int& k1) -> bool {   // false: no more segments
+    if (all_keys) {
+      k0 = 0;
+      k1 = a.N - 1;
+      return sidx == 0;
+    }
+    const int nv = variant == 1 ? 1 : a.F;
+    if (sidx == 0) {            // text prefix
+      k0 = 0;
+      k1 = a.off - 1;
+    } else if (sidx == 1) {     // first-frame sink
+      k0 = a.off;
+      k1 = a.sink ? a.off + a.P - 1 : a.off - 1;
+    } else if (sidx < 2 + nv) {
+      if (c_hi < 0) {           // no video row at all (cannot happen unless all_keys)
+        k0 = 0;
+        k1 = -1;
+      } else if (variant == 1) {
+        k0 = a.off + max(0, c_lo - a.w_s) * a.P;
+        k1 = a.off + min(a.F, c_hi + a.w_s + 1) * a.P - 1;
+      } else {
+        const int f = sidx - 2;
+        k0 = a.off + f * a.P + max(0, c_lo - a.w_t);
+        k1 = a.off + f * a.P + min(a.P - 1, c_hi + a.w_t);
+      }
+    } else if (sidx == 2 + nv) {  // text suffix
+      k0 = a.video_end;
+      k1 = a.N - 1;
+    } else {
+      return false;
+    }
+    return true;
+  };
+  auto profile_next = [&]() -> int {
+    while (pj > pjb) {
+      int k0, k1;
+      if (!profile_segment(pseg, k0, k1)) return kNoTile;
+      ++pseg;
+      if (k1 < k0) continue;
+      const int ja = k0 / BN, jb = k1 / BN;
+      if (jb < pj) continue;
+      pj = max(pj, ja);
+      pjb = jb;
+    }
+    return pj++;
+  };
+
+  // smallest key tile any of the lists still holds (they ascend), or kNoTile
+  auto peek = [&]() -> int {
+    if (MODE == kDense) return jdense < a.nk ? jdense : kNoTile;
+    if (MODE == kProfile) return profile_next();
+    int c = kNoTile;
+#pragma unroll
+    for (int s = 0; s < QT; ++s)
+      if (li[s] < le[s]) c = min(c, cols[li[s]]);
+    return c;
+  };
+  // consume `col` from every list whose head it is; returns whether this wave's tile keeps it
+  auto take = [&](int col) -> bool {
+    if (MODE != kSparse) {
+      ++jdense;     // (profile: the generator already advanced)
+      return true;
+    }
+    bool mine = false;
+#pragma unroll
+    for (int s = 0; s < QT; ++s) {
+      const bool use = li[s] < le[s] && cols[li[s]] == col;
+      li[s] += use ? 1 : 0;
+      if (s == my_sub) mine = use;
+    }
+    return mine;
+  };
 
   // ---- Q^T as the B operand: lane (g, r) holds Q[qrow][16 s + 8 g .. +8]
   bf16x8 qreg[QB][DS];
@@ -383,6 +474,12 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && QB == 1) ? 2 : 1) void attn_ke
   } else {
     col = peek();
   }
+  bool mine_cur = false, mine_next = false;
+  if (MODE == kSparse && QT > 1) {
+    mine_cur = col != kNoTile ? take(col) : false;
+    lcol1 = peek();
+    mine_next = lcol1 != kNoTile ? take(lcol1) : false;
+  }
   if (col != kNoTile) {
     load_tile(col);
     store_tile(0, col);
@@ -410,6 +507,14 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && QB == 1) ? 2 : 1) void attn_ke
       lcol1 = lcol2;
       lcol2 = list_at(lj + 3);
       ++lj;
+    } else if (MODE == kSparse) {
+      // merged lists run one step ahead: this tile and the next are already known, the
+      // one after is worked out now (its scalar loads complete during this tile)
+      mine = mine_cur;
+      next_col = lcol1;
+      mine_cur = mine_next;
+      lcol1 = peek();
+      mine_next = lcol1 != kNoTile ? take(lcol1) : false;
     } else {
       mine = take(col);
       next_col = peek();
@@ -575,6 +680,42 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && QB == 1) ? 2 : 1) void attn_ke
   }
 }
 
+// Groups the sampled rows by in-frame position for the temporal profiling variant:
+// order[] receives the indices 0..t-1 sorted by a coarse position bin (text rows
+// first).  One workgroup, counting sort with LDS atomics; the order inside a bin is
+// arbitrary, which is harmless because every result is written back to its own slot.
+constexpr int kOrderBins = 2048;
+__global__ __launch_bounds__(1024) void profile_order_kernel(const int32_t* rows, int t, int off,
+                                                             int video_end, int P, int32_t* order) {
+  __shared__ int hist[kOrderBins];
+  __shared__ int part[1024];
+  const int tid = threadIdx.x;
+  auto bin_of = [&](int n) -> int {
+    if (n < off || n >= video_end) return 0;
+    const int p = (n - off) % P;
+    return 1 + (int)(((long long)p * (kOrderBins - 1)) / P);
+  };
+  for (int i = tid; i < kOrderBins; i += 1024) hist[i] = 0;
+  __syncthreads();
+  for (int i = tid; i < t; i += 1024) atomicAdd(&hist[bin_of(rows[i])], 1);
+  __syncthreads();
+  // exclusive scan of the 2048 bins: two per thread, then Hillis-Steele over the pair sums
+  const int h0 = hist[2 * tid], h1 = hist[2 * tid + 1];
+  part[tid] = h0 + h1;
+  __syncthreads();
+  for (int step = 1; step < 1024; step <<= 1) {
+    const int add = tid >= step ? part[tid - step] : 0;
+    __syncthreads();
+    part[tid] += add;
+    __syncthreads();
+  }
+  const int base = part[tid] - (h0 + h1);
+  hist[2 * tid] = base;
+  hist[2 * tid + 1] = base + h0;
+  __syncthreads();
+  for (int i = tid; i < t; i += 1024) order[atomicAdd(&hist[bin_of(rows[i])], 1)] = i;
+}
+
 // MSE_s, MSE_t and the label of one head from the three profiled outputs
 // (Alg. 1, last block).  One workgroup per head, fixed-order tree reduction.
 __global__ __launch_bounds__(256) void profile_finalize_kernel(const float* ws, int BH, int t, int D,
@@ -615,13 +756,17 @@ __global__ __launch_bounds__(256) void profile_finalize_kernel(const float* ws, 
 #ifndef SVG_ATTN_QB
 #define SVG_ATTN_QB 1     // 32-query blocks per wavefront for the 128x64-tile kernels
 #endif
+#ifndef SVG_ATTN_NW
+#define SVG_ATTN_NW 4     // wavefronts per workgroup for the 128x64-tile kernels (4: one query tile, 8: two; 8 measured slower)
+#endif
 
 template <int D, int NW, int QB, int BN, int MODE>
 int launch_one(AttnArgs a, int rows_total, hipStream_t stream) {
   constexpr int BMW = 32 * QB * NW;
   a.nqt = (rows_total + BMW - 1) / BMW;
   a.total = (MODE == kProfile ? 3 : 1) * a.BH * a.nqt;
-  const unsigned grid = (unsigned)(((a.total + 7) / 8) * 8);
+  const unsigned grid = MODE == kProfile ? (unsigned)(24 * ((a.BH * a.nqt + 7) / 8))
+                                         : (unsigned)(((a.total + 7) / 8) * 8);
   (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
   hipLaunchKernelGGL((attn_kernel<D, NW, QB, BN, MODE>), dim3(grid), dim3(64 * NW), 0, stream, a);
   return hip_status(hipGetLastError());
@@ -631,8 +776,8 @@ int launch_one(AttnArgs a, int rows_total, hipStream_t stream) {
 template <int MODE>
 int dispatch(const Geo& g, const AttnArgs& a, int rows_total, hipStream_t stream) {
   if (g.bm == 128) {
-    return g.D == 128 ? launch_one<128, 4, SVG_ATTN_QB, 64, MODE>(a, rows_total, stream)
-                      : launch_one<64, 4, SVG_ATTN_QB, 64, MODE>(a, rows_total, stream);
+    return g.D == 128 ? launch_one<128, SVG_ATTN_NW, SVG_ATTN_QB, 64, MODE>(a, rows_total, stream)
+                      : launch_one<64, SVG_ATTN_NW, SVG_ATTN_QB, 64, MODE>(a, rows_total, stream);
   }
   return g.D == 128 ? launch_one<128, 1, 1, 32, MODE>(a, rows_total, stream)
                     : launch_one<64, 1, 1, 32, MODE>(a, rows_total, stream);
@@ -671,7 +816,15 @@ int launch_profile(const Geo& g, const void* q, const void* k, const void* v, co
   AttnArgs a = base_args(g, q, k, v, workspace);
   a.rows = rows;
   a.t = t;
-  int rc = dispatch<kProfile>(g, a, t, stream);
+  // workspace: three fp32 outputs [3][BH][t][D], then the position-grouped row order int32[t]
+  int32_t* order = reinterpret_cast<int32_t*>(workspace + (size_t)3 * a.BH * t * g.D);
+  (void)hipGetLastError();
+  hipLaunchKernelGGL(profile_order_kernel, dim3(1), dim3(1024), 0, stream, rows, t, g.off, g.video_end,
+                     g.P, order);
+  int rc = hip_status(hipGetLastError());
+  if (rc != SVG_OK) return rc;
+  a.order_t = order;
+  rc = dispatch<kProfile>(g, a, t, stream);
   if (rc != SVG_OK) return rc;
   (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
   hipLaunchKernelGGL(profile_finalize_kernel, dim3(a.BH), dim3(256), 0, stream, workspace, a.BH, t,
