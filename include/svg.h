@@ -66,9 +66,10 @@ const char* svg_last_hip_error(void);
 /* Library version, "major.minor". */
 const char* svg_version(void);
 
-/* Bytes of device workspace svg_profile_heads needs for `t` sampled rows
- * (three fp32 outputs of shape [B,H,t,D] and an int32[t] row order).  0 if shape
- * is invalid. */
+/* Bytes of device workspace svg_profile_heads needs for `t` sampled rows (fp32
+ * partial outputs of shape [B,H,t,D] for the spatial pass, the temporal pass and
+ * each key range of the unmasked pass, per-row softmax statistics of those ranges,
+ * and an int32[t] row order).  0 if shape is invalid. */
 size_t svg_workspace_bytes(const svg_shape_t* shape, int32_t t);
 
 /* Number of query tiles and key tiles: ceil(N/block_m), ceil(N/block_n). */

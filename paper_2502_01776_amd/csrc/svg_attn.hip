@@ -26,66 +26,17 @@
 // Softmax runs in fp32 with base-2 exponentials (scale * log2 e folded into one
 // FMA per element); P is rounded to bf16 for the second product; accumulation is
 // fp32; the running sum uses the unrounded P.
-#include "svg_internal.h"
+#include "svg_attn_common.h"
 
 namespace svg {
 
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef float f32x8 __attribute__((ext_vector_type(8)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-typedef int i32x4 __attribute__((ext_vector_type(4)));
+using namespace attn;
 
-enum Mode { kDense = 0, kSparse = 1, kProfile = 2 };
-
-constexpr int kCodeDrop = 0x7fffffff;   // key beyond N: never kept
-constexpr int kCodeKeep = 0x7ffffffe;   // text key / sink key: kept by every query
-constexpr float kNegBig = -1.0e30f;     // finite stand-in for -inf as the initial row maximum
-constexpr float kLazySum = 8192.0f;      // a lane's per-tile sum of exponentials above this forces a new reference maximum
-
-struct AttnArgs {
-  const __bf16* q;
-  const __bf16* k;
-  const __bf16* v;
-  void* o;                    // bf16 [B,H,N,D] (dense, sparse) or fp32 [3][BH][t][D] (profile)
-  const uint8_t* labels;      // sparse: per-head pattern, may be null
-  const int32_t* row_ptr[2];
-  const int32_t* col_idx[2];
-  const int32_t* rows;        // profile: sampled rows
-  const int32_t* order_t;     // profile: indices into rows[], grouped by in-frame position (temporal variant)
-  int t;                      // profile: number of sampled rows
-  int N, nq, nk, BH;
-  int nqt;                    // row groups (workgroups) per head: ceil(nq / tiles per workgroup); profile: ceil(t / rows per workgroup)
-  int reverse_q;              // process query tiles last-to-first (heavy text-suffix tiles first)
-  int total;                  // logical workgroups
-  float scale_log2;           // softmax scale * log2(e)
-  int off, video_end, F, P, w_s, w_t, sink;
-};
-
-template <int D>
-__device__ __forceinline__ int k_swizzle(int key) {
-  // XOR applied to the 16-byte piece index of a K row so that the 16 lanes served
-  // together by a ds_read_b128 hit 16 different 4-bank groups.
-  return D == 128 ? (key & 15) : ((key >> 1) & 7);
-}
-
-// Lanes l and l^32 own the two halves of one query's keys.  v_permlane32_swap with
-// both operands equal returns {x[l % 32], x[32 + l % 32]} in every lane, so the
-// combined maximum / sum needs no LDS traffic.
-__device__ __forceinline__ float both_halves_max(float x) {
-  const unsigned u = __float_as_uint(x);
-  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
-}
-__device__ __forceinline__ float both_halves_sum(float x) {
-  const unsigned u = __float_as_uint(x);
-  const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
-  return __uint_as_float(r[0]) + __uint_as_float(r[1]);
-}
+#ifndef SVG_ATTN_PF
+#define SVG_ATTN_PF 4      // LDS operand reads kept in flight ahead of the products
+#endif
 
 template <int D, int NW, int QB, int BN, int MODE>
 __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_kernel(AttnArgs a) {
@@ -106,7 +57,11 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
   constexpr int K_THREADS = SPLIT ? THREADS - V_UNITS : THREADS;
   constexpr int K_PER_THREAD = (K_PIECES + K_THREADS - 1) / K_THREADS;
   constexpr int V_PER_THREAD = SPLIT ? 1 : (V_UNITS + THREADS - 1) / THREADS;
-  constexpr int K_BYTES = BN * D * 2;
+  // K staging: row-major, rows padded by 16 bytes so that the 16 lanes served together
+  // by a ds_read_b128 of the A operand (16 consecutive keys, same channel piece) fall on
+  // different banks, while every operand address stays base + compile-time offset.
+  constexpr int K_ROW = D * 2 + 16;
+  constexpr int K_BYTES = BN * K_ROW;
   // V^T staging: [8-key group][d][8 keys], 16 bytes per (group, d): one ds_read_b128
   // is a whole A operand of the second product.  Group (kb, kk, g) holds the keys
   // 32 kb + 16 kk + 4 g + {0..3, 8..11}, i.e. the k-slots of half-wave g.  Inside a
@@ -128,16 +83,20 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
   // the query tiles that stream the same K/V share one L2.
   const int per_xcd = (a.total + 7) >> 3;
   const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
-  int bh, grp, variant = 0;
+  int bh, grp, variant = 0, chunk = 0;
   if (MODE == kProfile) {
-    // (head, row group) pairs are split into 8 contiguous chunks, one per XCD; inside a
-    // chunk the unmasked passes (every key tile) come first and the two masked passes
-    // (a fraction of the tiles) fill in behind them.  a.total = 3 * BH * nqt.
+    // (head, row group) pairs are split into 8 contiguous chunks, one per XCD.  Each pair
+    // has nsplit + 2 units of similar length: the unmasked pass cut into nsplit key
+    // ranges, the spatial pass and the temporal pass (both skip most key tiles).  Units
+    // are the outer index inside an XCD's chunk, so neighbouring workgroups stream the
+    // same keys for neighbouring row groups of one head.
     const int pairs = a.BH * a.nqt;
     const int pairs_per_xcd = (pairs + 7) >> 3;
-    variant = loc / pairs_per_xcd;
-    const int pair = xcd * pairs_per_xcd + (loc - variant * pairs_per_xcd);
-    if (variant > 2 || pair >= pairs) return;
+    const int unit = loc / pairs_per_xcd;
+    const int pair = xcd * pairs_per_xcd + (loc - unit * pairs_per_xcd);
+    if (unit >= a.nsplit + 2 || pair >= pairs) return;
+    variant = unit < a.nsplit ? 0 : unit - a.nsplit + 1;
+    chunk = unit < a.nsplit ? unit : 0;
     bh = pair / a.nqt;
     grp = pair - bh * a.nqt;
   } else {
@@ -220,9 +179,11 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
         win_span[qb] = 2u * (unsigned)w;
         atomicMin(&wg_range[0], c);
         atomicMax(&wg_range[1], c);
-      } else {
-        atomicOr(&wg_range[2], 1);
       }
+      // a text query attends to everything under both masks, so its masked outputs equal
+      // the unmasked one by definition: it adds nothing to either error, the finalize
+      // step skips it, and it need not widen this workgroup's key range
+
     }
   }
   // Key intervals that can hold a kept key for ANY row of the workgroup, ascending:
@@ -239,9 +200,11 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
   }
   int pseg = 0, pj = 0, pjb = -1;
   auto profile_segment = [&](int sidx, int& k0, int& k1) -> bool {   // false: no more segments
-    if (all_keys) {
-      k0 = 0;
-      k1 = a.N - 1;
+    if (all_keys) {          // unmasked pass: key tiles [chunk, chunk + 1) * nk / nsplit
+      const int t0 = (int)(((long long)chunk * a.nk) / a.nsplit);
+      const int t1 = (int)(((long long)(chunk + 1) * a.nk) / a.nsplit);
+      k0 = t0 * BN;
+      k1 = min(a.N, t1 * BN) - 1;
       return sidx == 0;
     }
     const int nv = variant == 1 ? 1 : a.F;
@@ -425,7 +388,7 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
           const int u = (tid - V_UNITS) + i * K_THREADS;
           if (K_PIECES % K_THREADS == 0 || u < K_PIECES) {
             const int key = u / CPR, c = u % CPR;
-            *reinterpret_cast<u32x4*>(kb + key * (D * 2) + ((c ^ k_swizzle<D>(key)) << 4)) = stg[i];
+            *reinterpret_cast<u32x4*>(kb + key * K_ROW + (c << 4)) = stg[i];
           }
         }
       }
@@ -434,7 +397,7 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
       for (int i = 0; i < K_PER_THREAD; ++i) {
         const int u = tid + i * THREADS;
         const int key = u / CPR, c = u % CPR;
-        *reinterpret_cast<u32x4*>(kb + key * (D * 2) + ((c ^ k_swizzle<D>(key)) << 4)) = kst[i];
+        *reinterpret_cast<u32x4*>(kb + key * K_ROW + (c << 4)) = kst[i];
       }
 #pragma unroll
       for (int i = 0; i < V_PER_THREAD; ++i) {
@@ -459,18 +422,30 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
     }
   };
 
-  // Tile cursor.  One query tile per workgroup (QT == 1): the list is walked with the
-  // entry two tiles ahead already requested, so no scalar load sits between one tile's
-  // barrier and the next tile's global loads.  Several query tiles per workgroup: their
-  // lists are merged on the fly (peek / take).
-  int lj = 0, lcol1 = kNoTile, lcol2 = kNoTile;
-  auto list_at = [&](int j) -> int { return j < le[0] ? cols[j] : kNoTile; };
+  // Tile cursor.  One query tile per workgroup (QT == 1): a ring holds the current tile
+  // and the next three, so no scalar load sits between one tile's barrier and the next
+  // tile's global loads.  (Reading a line of the tile three steps ahead to warm L2 was
+  // tried and measured slower.)
+  // Several query tiles per workgroup: their lists are merged on the fly (peek / take).
+  int lj = 0, lcol1 = kNoTile, lcol2 = kNoTile, lcol3 = kNoTile;
+  auto next_in_order = [&]() -> int {      // QT == 1: the next tile of this workgroup, any mode
+    if (MODE == kSparse) {
+      const int j = lj++;
+      return j < le[0] ? cols[j] : kNoTile;
+    }
+    return peek();       // dense: counter (take() advances it); profile: generator
+  };
   int col;
-  if (MODE == kSparse && QT == 1) {
+  if (QT == 1) {
     lj = li[0];
-    col = list_at(lj);
-    lcol1 = list_at(lj + 1);
-    lcol2 = list_at(lj + 2);
+    col = next_in_order();
+    if (MODE == kDense) ++jdense;
+    lcol1 = next_in_order();
+    if (MODE == kDense) ++jdense;
+    lcol2 = next_in_order();
+    if (MODE == kDense) ++jdense;
+    lcol3 = next_in_order();
+    if (MODE == kDense) ++jdense;
   } else {
     col = peek();
   }
@@ -486,8 +461,16 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
   }
   __syncthreads();
 
+  // Touch Q here so that its loads are known to have completed before the loop.  Without
+  // this the compiler's wait-count bookkeeping still sees them pending at the loop head
+  // and emits vmcnt waits in front of the first products of every iteration, which then
+  // wait for the NEXT tile's freshly issued global loads instead.
+#pragma unroll
+  for (int qb = 0; qb < QB; ++qb)
+#pragma unroll
+    for (int s = 0; s < DS; ++s) asm volatile("" ::"v"(qreg[qb][s]));
+
   int buf = 0;
-  const int swz = k_swizzle<D>(r);   // tile rows kb*32 + r: swizzle depends on r only
   // byte offset of channel d = 32 db + r inside a V^T group row (see store_v_unit)
   int v_off[DB];
 #pragma unroll
@@ -501,12 +484,13 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
   while (col != kNoTile) {
     bool mine;
     int next_col;
-    if (MODE == kSparse && QT == 1) {
+    if (QT == 1) {
       mine = true;
       next_col = lcol1;
       lcol1 = lcol2;
-      lcol2 = list_at(lj + 3);
-      ++lj;
+      lcol2 = lcol3;
+      lcol3 = next_in_order();
+      if (MODE == kDense) ++jdense;
     } else if (MODE == kSparse) {
       // merged lists run one step ahead: this tile and the next are already known, the
       // one after is worked out now (its scalar loads complete during this tile)
@@ -525,25 +509,44 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
       const unsigned char* kbuf = lds + buf * STAGE_BYTES;
       const unsigned char* vbuf = kbuf + K_BYTES;
 
-      // ---- S^T = K Q^T : each K operand read from LDS feeds QB products
+      // ---- S^T = K Q^T : each K operand read from LDS feeds QB products.
+      // Operand reads run PF products ahead of their use (a rolling window of PF operand
+      // registers), so after the first few the LDS latency is hidden behind the MFMAs
+      // instead of being paid at the start of every batch; the scheduling barriers pin
+      // the read / product interleave.
+      constexpr int PF = SVG_ATTN_PF;
+      constexpr int NS = KB * DS;          // operands of the first product, order (kb, s)
+      constexpr int NV = KB * 2 * DB;      // operands of the second product, order (kb, kk, db)
+      auto k_operand = [&](int i) -> bf16x8 {
+        const int kb = i / DS, s = i % DS;
+        return *reinterpret_cast<const bf16x8*>(kbuf + (kb * 32 + r) * K_ROW + ((2 * s + g) << 4));
+      };
+      auto v_operand = [&](int i) -> bf16x8 {
+        const int kg8 = (i / DB) * 2 + g, db = i % DB;     // i / DB = kb * 2 + kk
+        return *reinterpret_cast<const bf16x8*>(vbuf + kg8 * V_ROW + v_off[db]);
+      };
       f32x16 sacc[QB][KB];
+      bf16x8 opnd[PF];
 #pragma unroll
-      for (int kb = 0; kb < KB; ++kb) {
+      for (int i = 0; i < PF; ++i) opnd[i] = k_operand(i);
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
+      for (int i = 0; i < NS; ++i) {
+        const int kb = i / DS, s = i % DS;
+        const bf16x8 ka = opnd[i % PF];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-          for (int e = 0; e < 16; ++e) sacc[qb][kb][e] = 0.f;
-        const unsigned char* krow = kbuf + (kb * 32 + r) * (D * 2);
-        // keep the operand reads of one 32-key block from being hoisted above the
-        // products of the previous one (bounds the registers held by operands in flight)
-        if (kb > 0) __builtin_amdgcn_sched_barrier(0);
+        for (int qb = 0; qb < QB; ++qb) {
+          if (s == 0) {
 #pragma unroll
-        for (int s = 0; s < DS; ++s) {
-          const bf16x8 ka = *reinterpret_cast<const bf16x8*>(krow + (((2 * s + g) ^ swz) << 4));
-#pragma unroll
-          for (int qb = 0; qb < QB; ++qb)
-            sacc[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[qb][s], sacc[qb][kb], 0, 0, 0);
+            for (int e = 0; e < 16; ++e) sacc[qb][kb][e] = 0.f;
+          }
+          sacc[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[qb][s], sacc[qb][kb], 0, 0, 0);
         }
+        // refill the slot just consumed: next K operand, or (at the tail) the first V^T
+        // operands, which then arrive while the softmax runs
+        if (i + PF < NS) opnd[i % PF] = k_operand(i + PF);
+        else opnd[i % PF] = v_operand(i + PF - NS);
+        __builtin_amdgcn_sched_barrier(0);
       }
 
       bf16x8 pb[QB][KB][2];
@@ -622,21 +625,19 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
         l_run[qb] += l_loc;
       }
 
-      // ---- O^T += V^T P^T : each V^T operand read from LDS feeds QB products
+      // ---- O^T += V^T P^T : each V^T operand read from LDS feeds QB products.  The first
+      // PF operands were requested at the end of the first product (slot (NS + i) % PF).
 #pragma unroll
-      for (int kb = 0; kb < KB; ++kb)
+      for (int i = 0; i < NV; ++i) {
+        const int kbkk = i / DB, db = i % DB;
+        const bf16x8 va = opnd[(NS + i) % PF];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-          const int kg8 = kb * 4 + kk * 2 + g;
-          if (kb + kk > 0) __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int db = 0; db < DB; ++db) {
-            const bf16x8 va = *reinterpret_cast<const bf16x8*>(vbuf + kg8 * V_ROW + v_off[db]);
-#pragma unroll
-            for (int qb = 0; qb < QB; ++qb)
-              oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[qb][kb][kk], oacc[qb][db], 0, 0, 0);
-          }
-        }
+        for (int qb = 0; qb < QB; ++qb)
+          oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[qb][kbkk >> 1][kbkk & 1], oacc[qb][db], 0, 0, 0);
+        if (i + PF < NV) opnd[(NS + i) % PF] = v_operand(i + PF);
+        __builtin_amdgcn_sched_barrier(0);
+      }
     }
 
     if (next_col != kNoTile) store_tile(buf ^ 1, next_col);
@@ -652,7 +653,13 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
     const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
     if (MODE == kProfile) {
       if (qslot[qb] < a.t) {
-        float* op = static_cast<float*>(a.o) + (((size_t)variant * a.BH + bh) * a.t + qslot[qb]) * D;
+        // output slots: [0, nsplit) unmasked key ranges, nsplit spatial, nsplit + 1 temporal
+        const int slot = variant == 0 ? chunk : a.nsplit + variant - 1;
+        float* op = static_cast<float*>(a.o) + (((size_t)slot * a.BH + bh) * a.t + qslot[qb]) * D;
+        if (variant == 0 && g == 0) {
+          float2* st = a.stats + ((size_t)chunk * a.BH + bh) * a.t + qslot[qb];
+          *st = make_float2(m_run[qb], l_tot);
+        }
 #pragma unroll
         for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -716,18 +723,41 @@ __global__ __launch_bounds__(1024) void profile_order_kernel(const int32_t* rows
   for (int i = tid; i < t; i += 1024) order[atomicAdd(&hist[bin_of(rows[i])], 1)] = i;
 }
 
-// MSE_s, MSE_t and the label of one head from the three profiled outputs
-// (Alg. 1, last block).  One workgroup per head, fixed-order tree reduction.
-__global__ __launch_bounds__(256) void profile_finalize_kernel(const float* ws, int BH, int t, int D,
-                                                               uint8_t* labels, float* mse) {
+// MSE_s, MSE_t and the label of one head from the profiled outputs (Alg. 1, last
+// block).  The unmasked output of a row is first reassembled from its nsplit key
+// ranges: each range r holds its normalised output O_r, its reference maximum m_r and
+// its row sum l_r, and O_full = sum_r w_r O_r / sum_r w_r with
+// w_r = l_r * 2^((m_r - max_r m_r) * scale_log2).  Text query rows are skipped (both
+// masks keep every key for them, so they contribute exactly zero).  One workgroup per
+// head, fixed-order tree reduction: deterministic.
+__global__ __launch_bounds__(256) void profile_finalize_kernel(const float* ws, const float2* stats,
+                                                               const int32_t* rows, int BH, int t, int D,
+                                                               int nsplit, float scale_log2, int off,
+                                                               int video_end, uint8_t* labels, float* mse) {
   const int bh = blockIdx.x;
   const size_t per = (size_t)t * D;
-  const float* of = ws + ((size_t)0 * BH + bh) * per;
-  const float* os = ws + ((size_t)1 * BH + bh) * per;
-  const float* ot = ws + ((size_t)2 * BH + bh) * per;
+  const float* os = ws + ((size_t)nsplit * BH + bh) * per;
+  const float* ot = ws + ((size_t)(nsplit + 1) * BH + bh) * per;
   float acc_s = 0.f, acc_t = 0.f;
   for (size_t e = threadIdx.x; e < per; e += 256) {
-    const float f = of[e];
+    const int row = (int)(e / D);
+    const int n = rows[row];
+    if (n < off || n >= video_end) continue;
+    float m_max = -3.0e38f;
+    for (int r = 0; r < nsplit; ++r) {
+      const float2 st = stats[((size_t)r * BH + bh) * t + row];
+      if (st.y > 0.f) m_max = fmaxf(m_max, st.x);
+    }
+    float num = 0.f, den = 0.f;
+    for (int r = 0; r < nsplit; ++r) {
+      const float2 st = stats[((size_t)r * BH + bh) * t + row];
+      if (st.y > 0.f) {
+        const float w = st.y * __builtin_amdgcn_exp2f((st.x - m_max) * scale_log2);
+        num = __builtin_fmaf(w, ws[((size_t)r * BH + bh) * per + e], num);
+        den += w;
+      }
+    }
+    const float f = den > 0.f ? num / den : 0.f;
     const float ds = f - os[e], dt = f - ot[e];
     acc_s = __builtin_fmaf(ds, ds, acc_s);
     acc_t = __builtin_fmaf(dt, dt, acc_t);
@@ -764,8 +794,8 @@ template <int D, int NW, int QB, int BN, int MODE>
 int launch_one(AttnArgs a, int rows_total, hipStream_t stream) {
   constexpr int BMW = 32 * QB * NW;
   a.nqt = (rows_total + BMW - 1) / BMW;
-  a.total = (MODE == kProfile ? 3 : 1) * a.BH * a.nqt;
-  const unsigned grid = MODE == kProfile ? (unsigned)(24 * ((a.BH * a.nqt + 7) / 8))
+  a.total = (MODE == kProfile ? a.nsplit + 2 : 1) * a.BH * a.nqt;
+  const unsigned grid = MODE == kProfile ? (unsigned)(8 * (a.nsplit + 2) * ((a.BH * a.nqt + 7) / 8))
                                          : (unsigned)(((a.total + 7) / 8) * 8);
   (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
   hipLaunchKernelGGL((attn_kernel<D, NW, QB, BN, MODE>), dim3(grid), dim3(64 * NW), 0, stream, a);
@@ -816,8 +846,14 @@ int launch_profile(const Geo& g, const void* q, const void* k, const void* v, co
   AttnArgs a = base_args(g, q, k, v, workspace);
   a.rows = rows;
   a.t = t;
-  // workspace: three fp32 outputs [3][BH][t][D], then the position-grouped row order int32[t]
-  int32_t* order = reinterpret_cast<int32_t*>(workspace + (size_t)3 * a.BH * t * g.D);
+  // workspace: fp32 outputs [nsplit + 2][BH][t][D] (unmasked key ranges, spatial,
+  // temporal), range statistics float2 [nsplit][BH][t], row order int32 [t]
+  const int ns = profile_splits(g);
+  a.nsplit = ns;
+  const size_t out_floats = (size_t)(ns + 2) * a.BH * t * g.D;
+  float2* stats = reinterpret_cast<float2*>(workspace + out_floats);
+  int32_t* order = reinterpret_cast<int32_t*>(stats + (size_t)ns * a.BH * t);
+  a.stats = stats;
   (void)hipGetLastError();
   hipLaunchKernelGGL(profile_order_kernel, dim3(1), dim3(1024), 0, stream, rows, t, g.off, g.video_end,
                      g.P, order);
@@ -827,8 +863,8 @@ int launch_profile(const Geo& g, const void* q, const void* k, const void* v, co
   rc = dispatch<kProfile>(g, a, t, stream);
   if (rc != SVG_OK) return rc;
   (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
-  hipLaunchKernelGGL(profile_finalize_kernel, dim3(a.BH), dim3(256), 0, stream, workspace, a.BH, t,
-                     g.D, labels, mse);
+  hipLaunchKernelGGL(profile_finalize_kernel, dim3(a.BH), dim3(256), 0, stream, workspace, stats, rows,
+                     a.BH, t, g.D, ns, a.scale_log2, g.off, g.video_end, labels, mse);
   return hip_status(hipGetLastError());
 }
 

@@ -67,8 +67,7 @@ const char* svg_last_hip_error(void) { return hipGetErrorString(svg::g_last_hip_
 size_t svg_workspace_bytes(const svg_shape_t* shape, int32_t t) {
   Geo g;
   if (svg::make_geo(shape, &g) != SVG_OK || t <= 0) return 0;
-  // three fp32 outputs [B,H,t,D] plus the int32[t] row order of the temporal variant
-  return (size_t)3 * g.B * g.H * (size_t)t * g.D * sizeof(float) + (((size_t)t * 4 + 15) & ~(size_t)15);
+  return svg::profile_workspace_bytes(g, t);
 }
 
 int svg_tile_counts(const svg_shape_t* shape, int32_t* nq, int32_t* nk) {

@@ -22,6 +22,18 @@ struct Geo {
 // Checks sizes, D and tile shape.  Returns SVG_OK and fills g, or an error code.
 int make_geo(const svg_shape_t* s, Geo* g);
 
+// Key ranges the unmasked profiling pass is cut into (so that its workgroups are about
+// as long as those of the two masked passes, which skip most key tiles).
+inline int profile_splits(const Geo& g) { return g.nk >= 32 ? 4 : 1; }
+
+// Bytes of workspace svg_profile_heads uses for t rows.
+inline size_t profile_workspace_bytes(const Geo& g, int t) {
+  const size_t bh = (size_t)g.B * g.H;
+  const int ns = profile_splits(g);
+  return (size_t)(ns + 2) * bh * t * g.D * sizeof(float) + (size_t)ns * bh * t * 2 * sizeof(float) +
+         (((size_t)t * 4 + 15) & ~(size_t)15);
+}
+
 inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 // Remembers the most recent HIP error of the calling thread for svg_last_hip_error().
