@@ -77,6 +77,9 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
 
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE_BYTES];
   __shared__ __attribute__((aligned(16))) int key_code[MODE == kProfile ? 2 * BN : 4];
+  // profile: per staged tile {smallest coordinate code, largest, flags}; flags bit 0: some key
+  // is kept by every query, bit 1: some key is out of range, bit 2: coordinates span a wrap
+  __shared__ int tile_info[MODE == kProfile ? 2 * 4 : 4];
 
   // ---- which (head, row group) is this workgroup?  Consecutive logical ids are
   // placed on the same XCD (workgroups are dealt round-robin over the 8 XCDs), so
@@ -419,6 +422,25 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
         if (a.sink && fk == 0) code = kCodeKeep;
       }
       key_code[buf * BN + tid] = code;
+      // Summary of the tile for the wave-uniform shortcuts in the masking step.  The
+      // coordinate codes of consecutive keys ascend (frames) or ascend by one with a
+      // wrap at frame ends (positions), so first and last coordinate lane bound them.
+      const bool is_coord = code != kCodeKeep && code != kCodeDrop;
+      const unsigned long long coord_lanes = __builtin_amdgcn_ballot_w64(is_coord);
+      int flags = (__builtin_amdgcn_ballot_w64(code == kCodeKeep) != 0 ? 1 : 0) |
+                  (__builtin_amdgcn_ballot_w64(code == kCodeDrop) != 0 ? 2 : 0);
+      int cmin = 0, cmax = -1;          // empty coordinate range
+      if (coord_lanes != 0) {
+        const int first = __builtin_ctzll(coord_lanes), last = 63 - __builtin_clzll(coord_lanes);
+        cmin = __builtin_amdgcn_readlane(code, first);
+        cmax = __builtin_amdgcn_readlane(code, last);
+        if (variant == 2 && cmax - cmin != last - first) flags |= 4;    // wrapped: treat as mixed
+      }
+      if (tid == 0) {
+        tile_info[buf * 4 + 0] = cmin;
+        tile_info[buf * 4 + 1] = cmax;
+        tile_info[buf * 4 + 2] = flags;
+      }
     }
   };
 
@@ -505,6 +527,29 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
     }
     if (next_col != kNoTile) load_tile(next_col);
 
+    // profile: does this wavefront need the tile at all, and does it need per-element masks?
+    bool need_masks = MODE == kProfile;
+    if (MODE == kProfile) {
+      const int cmin = tile_info[buf * 4 + 0], cmax = tile_info[buf * 4 + 1], flags = tile_info[buf * 4 + 2];
+      bool lane_all = (flags & 6) == 0, lane_none = (flags & 5) == 0;
+#pragma unroll
+      for (int qb = 0; qb < QB; ++qb) {
+        if (cmax >= cmin) {       // the tile has coordinate keys
+          const bool in_lo = (unsigned)(cmin - win_lo[qb]) <= win_span[qb];
+          const bool in_hi = (unsigned)(cmax - win_lo[qb]) <= win_span[qb];
+          lane_all = lane_all && in_lo && in_hi;
+          // disjoint: the whole range lies below or above this row's window
+          const long long lo = win_lo[qb], hi = lo + (long long)win_span[qb];
+          lane_none = lane_none && (cmax < lo || cmin > hi);
+        } else {
+          lane_none = lane_none && (flags & 1) == 0;
+        }
+      }
+      const bool wave_all = __builtin_amdgcn_ballot_w64(!lane_all) == 0;
+      const bool wave_none = __builtin_amdgcn_ballot_w64(!lane_none) == 0;
+      if (wave_none) mine = false;          // no row of this wavefront keeps any key of the tile
+      need_masks = !wave_all;
+    }
     if (mine) {
       const unsigned char* kbuf = lds + buf * STAGE_BYTES;
       const unsigned char* vbuf = kbuf + K_BYTES;
@@ -514,7 +559,7 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
       // registers), so after the first few the LDS latency is hidden behind the MFMAs
       // instead of being paid at the start of every batch; the scheduling barriers pin
       // the read / product interleave.
-      constexpr int PF = SVG_ATTN_PF;
+      constexpr int PF = MODE == kProfile ? 2 : SVG_ATTN_PF;   // (the profile form is short of registers)
       constexpr int NS = KB * DS;          // operands of the first product, order (kb, s)
       constexpr int NV = KB * 2 * DB;      // operands of the second product, order (kb, kk, db)
       auto k_operand = [&](int i) -> bf16x8 {
@@ -553,7 +598,7 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
 #pragma unroll
       for (int qb = 0; qb < QB; ++qb) {
         // ---- masking.  sacc[kb][4 i + jj] belongs to key  col*BN + 32 kb + 8 i + 4 g + jj.
-        if (MODE == kProfile) {
+        if (MODE == kProfile && need_masks) {
 #pragma unroll
           for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -565,7 +610,7 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
                 if (!keep) sacc[qb][kb][4 * i + jj] = -INFINITY;
               }
             }
-        } else if (ragged && col == a.nk - 1) {
+        } else if (MODE != kProfile && ragged && col == a.nk - 1) {
           int lim = a.N - col * BN - 4 * g;     // keys with 32 kb + 8 i + jj >= lim are out of range
           // opaque to the optimiser: keeps this rarely taken masking code inside the
           // branch instead of being speculated into every tile
@@ -723,23 +768,25 @@ __global__ __launch_bounds__(1024) void profile_order_kernel(const int32_t* rows
   for (int i = tid; i < t; i += 1024) order[atomicAdd(&hist[bin_of(rows[i])], 1)] = i;
 }
 
-// MSE_s, MSE_t and the label of one head from the profiled outputs (Alg. 1, last
-// block).  The unmasked output of a row is first reassembled from its nsplit key
-// ranges: each range r holds its normalised output O_r, its reference maximum m_r and
-// its row sum l_r, and O_full = sum_r w_r O_r / sum_r w_r with
+// Squared errors of the two masked outputs against the unmasked one (Alg. 1, last
+// block), first stage: block (x, bh) sums kErrRows sampled rows of head bh and writes
+// one partial pair.  The unmasked output of a row is first reassembled from its nsplit
+// key ranges: each range r holds its normalised output O_r, its reference maximum m_r
+// and its row sum l_r, and O_full = sum_r w_r O_r / sum_r w_r with
 // w_r = l_r * 2^((m_r - max_r m_r) * scale_log2).  Text query rows are skipped (both
-// masks keep every key for them, so they contribute exactly zero).  One workgroup per
-// head, fixed-order tree reduction: deterministic.
-__global__ __launch_bounds__(256) void profile_finalize_kernel(const float* ws, const float2* stats,
-                                                               const int32_t* rows, int BH, int t, int D,
-                                                               int nsplit, float scale_log2, int off,
-                                                               int video_end, uint8_t* labels, float* mse) {
-  const int bh = blockIdx.x;
+// masks keep every key for them, so they contribute exactly zero).
+constexpr int kErrRows = 16;
+__global__ __launch_bounds__(256) void profile_error_kernel(const float* ws, const float2* stats,
+                                                            const int32_t* rows, int BH, int t, int D,
+                                                            int nsplit, float scale_log2, int off,
+                                                            int video_end, float2* partial) {
+  const int bh = blockIdx.y;
   const size_t per = (size_t)t * D;
   const float* os = ws + ((size_t)nsplit * BH + bh) * per;
   const float* ot = ws + ((size_t)(nsplit + 1) * BH + bh) * per;
+  const int row0 = blockIdx.x * kErrRows, row1 = min(t, row0 + kErrRows);
   float acc_s = 0.f, acc_t = 0.f;
-  for (size_t e = threadIdx.x; e < per; e += 256) {
+  for (size_t e = (size_t)row0 * D + threadIdx.x; e < (size_t)row1 * D; e += 256) {
     const int row = (int)(e / D);
     const int n = rows[row];
     if (n < off || n >= video_end) continue;
@@ -766,21 +813,35 @@ __global__ __launch_bounds__(256) void profile_finalize_kernel(const float* ws, 
   red_s[threadIdx.x] = acc_s;
   red_t[threadIdx.x] = acc_t;
   __syncthreads();
-  for (int step = 128; step > 0; step >>= 1) {
+  for (int step = 128; step > 0; step >>= 1) {      // fixed order: deterministic
     if (threadIdx.x < step) {
       red_s[threadIdx.x] += red_s[threadIdx.x + step];
       red_t[threadIdx.x] += red_t[threadIdx.x + step];
     }
     __syncthreads();
   }
-  if (threadIdx.x == 0) {
-    const float ms = red_s[0] / (float)per, mt = red_t[0] / (float)per;
-    if (mse) {
-      mse[2 * bh + 0] = ms;
-      mse[2 * bh + 1] = mt;
-    }
-    labels[bh] = ms < mt ? SVG_HEAD_SPATIAL : SVG_HEAD_TEMPORAL;
+  if (threadIdx.x == 0) partial[(size_t)bh * gridDim.x + blockIdx.x] = make_float2(red_s[0], red_t[0]);
+}
+
+// Second stage: MSE_s, MSE_t and the label of one head from its partial sums, added in
+// index order (deterministic).  label = spatial iff MSE_s < MSE_t (Alg. 1).
+__global__ __launch_bounds__(64) void profile_label_kernel(const float2* partial, int n_partial, int t, int D,
+                                                           uint8_t* labels, float* mse) {
+  const int bh = blockIdx.x;
+  if (threadIdx.x != 0) return;
+  float sum_s = 0.f, sum_t = 0.f;
+  for (int i = 0; i < n_partial; ++i) {
+    const float2 p = partial[(size_t)bh * n_partial + i];
+    sum_s += p.x;
+    sum_t += p.y;
   }
+  const float per = (float)t * (float)D;
+  const float ms = sum_s / per, mt = sum_t / per;
+  if (mse) {
+    mse[2 * bh + 0] = ms;
+    mse[2 * bh + 1] = mt;
+  }
+  labels[bh] = ms < mt ? SVG_HEAD_SPATIAL : SVG_HEAD_TEMPORAL;
 }
 
 #ifndef SVG_ATTN_QB
@@ -847,12 +908,15 @@ int launch_profile(const Geo& g, const void* q, const void* k, const void* v, co
   a.rows = rows;
   a.t = t;
   // workspace: fp32 outputs [nsplit + 2][BH][t][D] (unmasked key ranges, spatial,
-  // temporal), range statistics float2 [nsplit][BH][t], row order int32 [t]
+  // temporal), range statistics float2 [nsplit][BH][t], partial error sums float2
+  // [BH][ceil(t/16)], row order int32 [t]
   const int ns = profile_splits(g);
   a.nsplit = ns;
   const size_t out_floats = (size_t)(ns + 2) * a.BH * t * g.D;
   float2* stats = reinterpret_cast<float2*>(workspace + out_floats);
-  int32_t* order = reinterpret_cast<int32_t*>(stats + (size_t)ns * a.BH * t);
+  const int n_partial = (t + kErrRows - 1) / kErrRows;
+  float2* partial = stats + (size_t)ns * a.BH * t;
+  int32_t* order = reinterpret_cast<int32_t*>(partial + (size_t)a.BH * n_partial);
   a.stats = stats;
   (void)hipGetLastError();
   hipLaunchKernelGGL(profile_order_kernel, dim3(1), dim3(1024), 0, stream, rows, t, g.off, g.video_end,
@@ -863,8 +927,12 @@ int launch_profile(const Geo& g, const void* q, const void* k, const void* v, co
   rc = dispatch<kProfile>(g, a, t, stream);
   if (rc != SVG_OK) return rc;
   (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
-  hipLaunchKernelGGL(profile_finalize_kernel, dim3(a.BH), dim3(256), 0, stream, workspace, stats, rows,
-                     a.BH, t, g.D, ns, a.scale_log2, g.off, g.video_end, labels, mse);
+  hipLaunchKernelGGL(profile_error_kernel, dim3(n_partial, a.BH), dim3(256), 0, stream, workspace, stats,
+                     rows, a.BH, t, g.D, ns, a.scale_log2, g.off, g.video_end, partial);
+  rc = hip_status(hipGetLastError());
+  if (rc != SVG_OK) return rc;
+  hipLaunchKernelGGL(profile_label_kernel, dim3(a.BH), dim3(64), 0, stream, partial, n_partial, t, g.D,
+                     labels, mse);
   return hip_status(hipGetLastError());
 }
 

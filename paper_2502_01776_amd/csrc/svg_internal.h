@@ -31,7 +31,7 @@ inline size_t profile_workspace_bytes(const Geo& g, int t) {
   const size_t bh = (size_t)g.B * g.H;
   const int ns = profile_splits(g);
   return (size_t)(ns + 2) * bh * t * g.D * sizeof(float) + (size_t)ns * bh * t * 2 * sizeof(float) +
-         (((size_t)t * 4 + 15) & ~(size_t)15);
+         bh * (size_t)((t + 15) / 16) * 2 * sizeof(float) + (((size_t)t * 4 + 15) & ~(size_t)15);
 }
 
 inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
