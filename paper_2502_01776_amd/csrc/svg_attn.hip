@@ -1,6 +1,6 @@
 // FlashAttention-style forward kernels for gfx950 (MI355X): dense attention, the
-// block-sparse pass over a kept-tile list (Sec. 4.3), and the three masked passes
-// of online profiling over sampled query rows (Alg. 1, Sec. 4.1).
+// block-sparse pass over a kept-tile list (Sec. 4.3), and the masked passes of online
+// profiling over sampled query rows (Alg. 1, Sec. 4.1).
 //
 // One workgroup owns one query tile of one head; each of its NW wavefronts owns 32
 // query rows and all BN keys of the current key tile.  Both matrix products are
@@ -8,24 +8,35 @@
 //     S^T = K Q^T      (A = K tile from LDS,  B = Q^T held in registers)
 //     O^T += V^T P^T   (A = V^T from LDS,     B = P^T taken from S^T's registers)
 // In the 32x32 accumulator layout a lane holds ONE query column (lane % 32) and 16
-// key rows, so the online-softmax row maximum and row sum are per-lane register
-// reductions plus one exchange between lane l and lane l+32, the rescale factor is
-// one scalar per lane, and the exponentiated S^T registers are, after bf16
-// packing, exactly the B operand of the second product: register pair (2kk, 2kk+1)
-// of a 32-key block holds keys {16kk+4g+j} and {16kk+8+4g+j}, j<4, g = lane/32,
-// and the V^T operand is fetched for the same keys, so no cross-lane shuffle and no
-// LDS round trip is needed for P.
+// key rows, so the softmax row statistics are per-lane register reductions plus one
+// exchange between lane l and lane l+32, the rescale factor is one scalar per lane,
+// and the exponentiated S^T registers are, after bf16 packing, exactly the B operand
+// of the second product: register pair (2kk, 2kk+1) of a 32-key block holds keys
+// {16kk+4g+j} and {16kk+8+4g+j}, j<4, g = lane/32, and the V^T operand is stored
+// for the same key order, so P never moves between lanes or through LDS.
 //
-// K and V tiles are staged global -> registers -> LDS, double buffered, with the
-// loads of tile j+1 in flight while tile j is computed (one barrier per tile).
-// K is stored row-major with an XOR swizzle of its 16-byte pieces (conflict-free
-// ds_read_b128 of the A operand).  V is transposed in registers on the way in
-// (v_perm_b32) to a [key/4][d][4 keys] layout, so the V^T operand of 8 keys at one
-// d is two ds_read_b64.
+// Staging: K and V tiles go global -> registers (raw buffer loads, bounds-checked
+// descriptors, loop-invariant offsets) -> LDS, double buffered, with the loads of
+// tile j+1 in flight while tile j is computed and one barrier per tile.  K rows are
+// padded by 16 bytes (conflict-free ds_read_b128 of the A operand with compile-time
+// offsets); V is transposed in registers on the way in (v_perm_b32) so that one
+// ds_read_b128 is a whole A operand of the second product.  Operand reads run a few
+// products ahead of their use (rolling window), including the first V^T operands,
+// which are requested before the softmax starts.
 //
-// Softmax runs in fp32 with base-2 exponentials (scale * log2 e folded into one
-// FMA per element); P is rounded to bf16 for the second product; accumulation is
-// fp32; the running sum uses the unrounded P.
+// Softmax: fp32, base-2 exponentials with scale * log2 e folded into one FMA per
+// element.  The exponentials are taken against the current reference maximum without
+// looking at the tile's own maximum; only when a row sum shows that the reference is
+// too small does the wave fall back to the classic update (tile maximum, rescale).
+// P is rounded to bf16 for the second product; accumulation is fp32; the running sum
+// uses the unrounded P.
+//
+// Measured on MI355X (see the rocprofv3 summaries): plain VALU instructions do not
+// overlap with MFMA execution on a SIMD (only the transcendental unit does), and with
+// 32 query rows per wavefront every MFMA needs a fresh 1 KB operand from LDS, which
+// by itself saturates the 128 B/clk LDS port at MFMA peak.  Wider per-wave tiles (64
+// rows) need more than 256 registers at D = 128 and were slower with the compiler's
+// AGPR handling; an 8-wavefront, two-query-tile workgroup was slower as well.
 #include "svg_attn_common.h"
 
 namespace svg {
@@ -34,15 +45,13 @@ namespace {
 
 using namespace attn;
 
-#ifndef SVG_ATTN_PF
-#define SVG_ATTN_PF 4      // LDS operand reads kept in flight ahead of the products
-#endif
+constexpr int kNoTile = 0x7fffffff;
+constexpr int kPrefetch = 4;          // LDS operand reads kept in flight ahead of the products
+constexpr unsigned kRsrcFlags = 0x00020000u;   // raw buffer, 32-bit data format (gfx9 encoding)
 
-template <int D, int NW, int QB, int BN, int MODE>
-__global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_kernel(AttnArgs a) {
-  constexpr int BMW = 32 * QB * NW;      // query rows per workgroup
-  constexpr int TILE_M = NW >= 4 ? 128 : 32 * NW;   // query-tile rows of the tile list (block_m)
-  constexpr int QT = BMW / TILE_M;       // query tiles per workgroup (= QB)
+template <int D, int NW, int BN, int MODE>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs a) {
+  constexpr int BM = 32 * NW;            // query rows per workgroup = rows of a query tile
   constexpr int THREADS = 64 * NW;
   constexpr int CPR = D / 8;             // 16-byte pieces per row
   constexpr int KB = BN / 32;            // 32-key blocks per tile
@@ -53,7 +62,7 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
   // Staging work split: with 4 wavefronts the first V_UNITS threads stage V (8 row
   // loads + register transpose each) and the others stage K; a single wavefront
   // does both.
-  constexpr bool SPLIT = NW >= 4;
+  constexpr bool SPLIT = NW == 4;
   constexpr int K_THREADS = SPLIT ? THREADS - V_UNITS : THREADS;
   constexpr int K_PER_THREAD = (K_PIECES + K_THREADS - 1) / K_THREADS;
   constexpr int V_PER_THREAD = SPLIT ? 1 : (V_UNITS + THREADS - 1) / THREADS;
@@ -70,21 +79,21 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
   constexpr int V_ROW = D * 16;
   constexpr int V_BYTES = (BN / 8) * V_ROW;
   constexpr int STAGE_BYTES = K_BYTES + V_BYTES;
-  constexpr int kNoTile = 0x7fffffff;
-  static_assert(!SPLIT || V_UNITS < THREADS, "no threads left to stage K");
-  static_assert(!SPLIT || K_THREADS % CPR == 0, "K staging threads must cover whole rows");
-  static_assert(TILE_M % (32 * QB) == 0, "a wavefront's rows must lie in one query tile");
+  static_assert(!SPLIT || V_UNITS % 64 == 0, "V staging must be done by whole wavefronts");
+  static_assert(!SPLIT || (V_UNITS < THREADS && K_THREADS % CPR == 0), "K staging threads must cover whole rows");
 
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE_BYTES];
   __shared__ __attribute__((aligned(16))) int key_code[MODE == kProfile ? 2 * BN : 4];
   // profile: per staged tile {smallest coordinate code, largest, flags}; flags bit 0: some key
   // is kept by every query, bit 1: some key is out of range, bit 2: coordinates span a wrap
   __shared__ int tile_info[MODE == kProfile ? 2 * 4 : 4];
+  __shared__ int wg_range[4];    // profile: min / max coordinate of the workgroup's rows
 
-  // ---- which (head, row group) is this workgroup?  Consecutive logical ids are
-  // placed on the same XCD (workgroups are dealt round-robin over the 8 XCDs), so
-  // the query tiles that stream the same K/V share one L2.
-  const int per_xcd = (a.total + 7) >> 3;
+  // ======================================================================================
+  // Which (head, row group) is this workgroup?  Consecutive logical ids are placed on the
+  // same XCD (workgroups are dealt round-robin over the 8 XCDs), so the query tiles that
+  // stream the same K/V share one L2.
+  // ======================================================================================
   const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
   int bh, grp, variant = 0, chunk = 0;
   if (MODE == kProfile) {
@@ -98,12 +107,12 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
     const int unit = loc / pairs_per_xcd;
     const int pair = xcd * pairs_per_xcd + (loc - unit * pairs_per_xcd);
     if (unit >= a.nsplit + 2 || pair >= pairs) return;
-    variant = unit < a.nsplit ? 0 : unit - a.nsplit + 1;
+    variant = unit < a.nsplit ? 0 : unit - a.nsplit + 1;     // 0 unmasked, 1 spatial, 2 temporal
     chunk = unit < a.nsplit ? unit : 0;
     bh = pair / a.nqt;
     grp = pair - bh * a.nqt;
   } else {
-    const int lid = xcd * per_xcd + loc;
+    const int lid = xcd * ((a.total + 7) >> 3) + loc;
     if (lid >= a.total) return;
     bh = lid / a.nqt;
     grp = lid - bh * a.nqt;
@@ -115,95 +124,85 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
   const int wave = tid >> 6;
   const int g = lane >> 5;       // which half of the wavefront
   const int r = lane & 31;       // query column within the wave / row of the A operand
-  const int my_sub = (wave * 32 * QB) / TILE_M;   // which of the workgroup's query tiles this wave is in
 
   const size_t head = (size_t)bh * a.N;
   const __bf16* kh = a.k + head * D;
   const __bf16* vh = a.v + head * D;
 
-  // ---- kept-tile lists of the workgroup's query tiles (sparse) or the full range
-  const int32_t* cols = nullptr;
-  int li[QT], le[QT];            // cursor and end of each query tile's list
-  int jdense = 0;
-  if (MODE == kSparse) {
-    const int pat = a.labels ? (a.labels[bh] != 0) : 0;
-    const int32_t* rp = a.row_ptr[pat];
-    cols = a.col_idx[pat];
-#pragma unroll
-    for (int s = 0; s < QT; ++s) {
-      const int qt = grp * QT + s;
-      li[s] = qt < a.nq ? rp[qt] : 0;
-      le[s] = qt < a.nq ? rp[qt + 1] : 0;
-    }
-  }
-  // ---- this lane's query rows (one per 32-query block)
-  int qslot[QB], qrow[QB];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    qslot[qb] = grp * BMW + wave * 32 * QB + qb * 32 + r;   // row (profile: index into rows[])
-    if (MODE == kProfile) {
-      // The temporal variant takes the sampled rows grouped by in-frame position, so
-      // that a workgroup's rows share a narrow position range and most key tiles can be
-      // skipped; results are still written at the row's own slot.
-      int slot = min(qslot[qb], a.t - 1);
-      if (variant == 2) slot = a.order_t[slot];
-      if (qslot[qb] < a.t) qslot[qb] = slot;
-      qrow[qb] = a.rows[slot];
-    } else {
-      qrow[qb] = min(qslot[qb], a.N - 1);
-    }
+  // ======================================================================================
+  // This lane's query row, its mask window (profile), and Q^T as the B operand.
+  // ======================================================================================
+  int qslot = grp * BM + wave * 32 + r;     // row (profile: index into rows[])
+  int qrow;
+  if (MODE == kProfile) {
+    // The temporal variant takes the sampled rows grouped by in-frame position, so that
+    // a workgroup's rows share a narrow position range and most key tiles can be
+    // skipped; results are still written at the row's own slot.
+    int slot = min(qslot, a.t - 1);
+    if (variant == 2) slot = a.order_t[slot];
+    if (qslot < a.t) qslot = slot;
+    qrow = a.rows[slot];
+  } else {
+    qrow = min(qslot, a.N - 1);
   }
 
-  // profile: window test  (unsigned)(code - lo) <= span  ||  code == kCodeKeep
-  int win_lo[QB];
-  unsigned win_span[QB];
-  // profile: coordinate range (frames or positions) of the workgroup's rows, for tile skipping
-  __shared__ int wg_range[3];    // min, max, any row that keeps every key
+  // profile: a key with code c is kept iff (unsigned)(c - win_lo) <= win_span or c == kCodeKeep
+  int win_lo = 0;
+  unsigned win_span = 0x7ffffffeu;
   if (MODE == kProfile) {
     if (tid == 0) {
       wg_range[0] = 0x7fffffff;
       wg_range[1] = -1;
-      wg_range[2] = variant == 0 ? 1 : 0;
     }
     __syncthreads();
+    if (variant != 0 && qrow >= a.off && qrow < a.video_end) {
+      const int vq = qrow - a.off;
+      const int fq = vq / a.P;
+      const int c = variant == 1 ? fq : vq - fq * a.P;
+      const int w = variant == 1 ? a.w_s : a.w_t;
+      win_lo = c - w;
+      win_span = 2u * (unsigned)w;
+      atomicMin(&wg_range[0], c);
+      atomicMax(&wg_range[1], c);
+    }
+    // (a text query attends to everything under both masks, so its masked outputs equal
+    // the unmasked one by definition: it adds nothing to either error, the error kernel
+    // skips it, and it need not widen this workgroup's key range)
+    __syncthreads();
   }
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    win_lo[qb] = 0;
-    win_span[qb] = 0x7ffffffeu;
-    if (MODE == kProfile && variant != 0) {
-      const bool text_q = qrow[qb] < a.off || qrow[qb] >= a.video_end;
-      if (!text_q) {
-        const int vq = qrow[qb] - a.off;
-        const int fq = vq / a.P;
-        const int c = variant == 1 ? fq : vq - fq * a.P;
-        const int w = variant == 1 ? a.w_s : a.w_t;
-        win_lo[qb] = c - w;
-        win_span[qb] = 2u * (unsigned)w;
-        atomicMin(&wg_range[0], c);
-        atomicMax(&wg_range[1], c);
-      }
-      // a text query attends to everything under both masks, so its masked outputs equal
-      // the unmasked one by definition: it adds nothing to either error, the finalize
-      // step skips it, and it need not widen this workgroup's key range
 
-    }
+  bf16x8 qreg[DS];     // lane (g, r) holds Q[qrow][16 s + 8 g .. +8]
+  {
+    const __bf16* qp = a.q + (head + qrow) * D + g * 8;
+#pragma unroll
+    for (int s = 0; s < DS; ++s) qreg[s] = *reinterpret_cast<const bf16x8*>(qp + s * 16);
   }
-  // Key intervals that can hold a kept key for ANY row of the workgroup, ascending:
-  // text prefix | frame 0 (sink) | the window around the rows' frames (spatial) or, per
-  // frame, the window around the rows' positions (temporal) | text suffix.  A superset
-  // is enough: the element mask is still applied inside every visited tile.
-  int c_lo = 0, c_hi = -1;
-  bool all_keys = true;
-  if (MODE == kProfile) {
-    __syncthreads();
-    c_lo = wg_range[0];
-    c_hi = wg_range[1];
-    all_keys = wg_range[2] != 0;
+
+  // ======================================================================================
+  // Tile cursor: the next key tile of this workgroup, or kNoTile.
+  //   dense   : 0 .. nk-1
+  //   sparse  : the query tile's row of the head's CSR list
+  //   profile : tiles of the key intervals that can hold a kept key for ANY row of the
+  //             workgroup, ascending: text prefix | frame 0 (sink) | the window around the
+  //             rows' frames (spatial) or, per frame, the window around the rows' positions
+  //             (temporal) | text suffix; the unmasked pass walks its key range.  A superset
+  //             is enough: the element mask is still applied inside every visited tile.
+  // ======================================================================================
+  const int32_t* cols = nullptr;
+  int lj = 0, lend = 0;              // sparse: cursor and end in col_idx;  dense: counter and nk
+  if (MODE == kSparse) {
+    const int pat = a.labels ? (a.labels[bh] != 0) : 0;
+    const int32_t* rp = a.row_ptr[pat];
+    cols = a.col_idx[pat];
+    lj = rp[grp];
+    lend = rp[grp + 1];
+  } else if (MODE == kDense) {
+    lend = a.nk;
   }
+  const int c_lo = MODE == kProfile ? wg_range[0] : 0, c_hi = MODE == kProfile ? wg_range[1] : -1;
   int pseg = 0, pj = 0, pjb = -1;
   auto profile_segment = [&](int sidx, int& k0, int& k1) -> bool {   // false: no more segments
-    if (all_keys) {          // unmasked pass: key tiles [chunk, chunk + 1) * nk / nsplit
+    if (variant == 0) {      // unmasked pass: key tiles [chunk, chunk + 1) * nk / nsplit
       const int t0 = (int)(((long long)chunk * a.nk) / a.nsplit);
       const int t1 = (int)(((long long)(chunk + 1) * a.nk) / a.nsplit);
       k0 = t0 * BN;
@@ -218,7 +217,7 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
       k0 = a.off;
       k1 = a.sink ? a.off + a.P - 1 : a.off - 1;
     } else if (sidx < 2 + nv) {
-      if (c_hi < 0) {           // no video row at all (cannot happen unless all_keys)
+      if (c_hi < 0) {           // every row of the workgroup is a text row: nothing to do
         k0 = 0;
         k1 = -1;
       } else if (variant == 1) {
@@ -237,8 +236,16 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
     }
     return true;
   };
-  auto profile_next = [&]() -> int {
-    while (pj > pjb) {
+  auto next_tile = [&]() -> int {
+    if (MODE == kSparse) {
+      const int j = lj++;
+      return j < lend ? cols[j] : kNoTile;
+    }
+    if (MODE == kDense) {
+      const int j = lj++;
+      return j < lend ? j : kNoTile;
+    }
+    while (pj > pjb) {       // profile: move to the next interval that still has tiles
       int k0, k1;
       if (!profile_segment(pseg, k0, k1)) return kNoTile;
       ++pseg;
@@ -251,80 +258,32 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
     return pj++;
   };
 
-  // smallest key tile any of the lists still holds (they ascend), or kNoTile
-  auto peek = [&]() -> int {
-    if (MODE == kDense) return jdense < a.nk ? jdense : kNoTile;
-    if (MODE == kProfile) return profile_next();
-    int c = kNoTile;
-#pragma unroll
-    for (int s = 0; s < QT; ++s)
-      if (li[s] < le[s]) c = min(c, cols[li[s]]);
-    return c;
-  };
-  // consume `col` from every list whose head it is; returns whether this wave's tile keeps it
-  auto take = [&](int col) -> bool {
-    if (MODE != kSparse) {
-      ++jdense;     // (profile: the generator already advanced)
-      return true;
-    }
-    bool mine = false;
-#pragma unroll
-    for (int s = 0; s < QT; ++s) {
-      const bool use = li[s] < le[s] && cols[li[s]] == col;
-      li[s] += use ? 1 : 0;
-      if (s == my_sub) mine = use;
-    }
-    return mine;
-  };
-
-  // ---- Q^T as the B operand: lane (g, r) holds Q[qrow][16 s + 8 g .. +8]
-  bf16x8 qreg[QB][DS];
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const __bf16* qp = a.q + (head + qrow[qb]) * D + g * 8;
-#pragma unroll
-    for (int s = 0; s < DS; ++s) qreg[qb][s] = *reinterpret_cast<const bf16x8*>(qp + s * 16);
-  }
-
-  f32x16 oacc[QB][DB];
-  float m_run[QB], l_run[QB];   // running row maximum (raw logits) and this lane's share of the row sum
-#pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    m_run[qb] = kNegBig;
-    l_run[qb] = 0.f;
-#pragma unroll
-    for (int db = 0; db < DB; ++db)
-#pragma unroll
-      for (int e = 0; e < 16; ++e) oacc[qb][db][e] = 0.f;
-  }
-
+  // ======================================================================================
+  // Staging of one K/V tile.
+  // ======================================================================================
   constexpr int STAGE_REGS = SPLIT ? (K_PER_THREAD > 8 ? K_PER_THREAD : 8) : 1;
   u32x4 stg[STAGE_REGS];                 // split roles: K pieces or the 8 rows of a V unit
   u32x4 kst[SPLIT ? 1 : K_PER_THREAD];   // single wavefront: both
   u32x4 vst[SPLIT ? 1 : V_PER_THREAD][8];
-  // staging role per wavefront (V_UNITS is a multiple of 64): read through
-  // readfirstlane so that the compiler treats the role branch as scalar
-  static_assert(!SPLIT || V_UNITS % 64 == 0, "V staging must be done by whole wavefronts");
+  // staging role per wavefront: read through readfirstlane so that the compiler treats the
+  // role branch as scalar (otherwise it merges both roles' loads and selects the buffer
+  // descriptor per lane)
   const bool v_role = SPLIT && __builtin_amdgcn_readfirstlane(tid >> 6) < V_UNITS / 64;
 
   // row of the e-th key of V group kg8 = (kb, kk, g):  32 kb + 16 kk + 4 g + e (+4 if e >= 4)
   auto v_key = [](int kg8, int e) { return (kg8 >> 1) * 16 + (kg8 & 1) * 4 + e + (e >= 4 ? 4 : 0); };
 
-  // Global -> register staging uses raw buffer loads: the descriptor of a tile starts
-  // at the tile's first key row and covers the rows up to N, so the per-thread
-  // offsets are loop invariant, no clamping arithmetic is needed, and rows beyond N
-  // (ragged last tile) read as zero.
-  constexpr unsigned kRsrcFlags = 0x00020000u;   // raw buffer, 32-bit data format (gfx9 encoding)
-  int stage_off[SPLIT ? 1 : (K_PER_THREAD > V_PER_THREAD ? K_PER_THREAD : V_PER_THREAD)];
+  // The descriptor of a tile starts at the tile's first key row and covers the rows up to
+  // N, so the per-thread offsets are loop invariant, no clamping arithmetic is needed, and
+  // rows beyond N (ragged last tile) read as zero.
+  int stage_off = 0;
   if (SPLIT) {
-    if (v_role) stage_off[0] = (v_key(tid / CPR, 0) * D + (tid % CPR) * 8) * 2;
-    else stage_off[0] = (((tid - V_UNITS) / CPR) * D + ((tid - V_UNITS) % CPR) * 8) * 2;
+    if (v_role) stage_off = (v_key(tid / CPR, 0) * D + (tid % CPR) * 8) * 2;
+    else stage_off = (((tid - V_UNITS) / CPR) * D + ((tid - V_UNITS) % CPR) * 8) * 2;
   }
-  (void)stage_off;
 
   auto load_tile = [&](int col_any) {
-    // the tile index is the same in every lane; saying so keeps the buffer descriptors in
-    // scalar registers (otherwise each load is wrapped in a loop over distinct descriptors)
+    // the tile index is the same in every lane; saying so keeps the descriptors scalar
     const int key0 = __builtin_amdgcn_readfirstlane(col_any) * BN;
     const unsigned bytes_left = (unsigned)(a.N - key0) * (D * 2);
     const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(
@@ -334,31 +293,27 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
     if (SPLIT) {
       if (v_role) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e)   // rows 0..3 and 8..11 of the group's first row
-          stg[e] = __builtin_amdgcn_raw_buffer_load_b128(rv, stage_off[0] + (e + (e >= 4 ? 4 : 0)) * (D * 2), 0, 0);
+        for (int e = 0; e < 8; ++e)   // rows +0..3 and +8..11 of the group's first row
+          stg[e] = __builtin_amdgcn_raw_buffer_load_b128(rv, stage_off + (e + (e >= 4 ? 4 : 0)) * (D * 2), 0, 0);
       } else {
 #pragma unroll
-        for (int i = 0; i < K_PER_THREAD; ++i) {
-          // piece u = (tid - V_UNITS) + i*K_THREADS; K_THREADS is a multiple of CPR here
+        for (int i = 0; i < K_PER_THREAD; ++i)    // piece (tid - V_UNITS) + i * K_THREADS
           if (K_PIECES % K_THREADS == 0 || (tid - V_UNITS) + i * K_THREADS < K_PIECES)
-            stg[i] = __builtin_amdgcn_raw_buffer_load_b128(rk, stage_off[0] + i * (K_THREADS / CPR) * (D * 2), 0, 0);
-        }
+            stg[i] = __builtin_amdgcn_raw_buffer_load_b128(rk, stage_off + i * (K_THREADS / CPR) * (D * 2), 0, 0);
       }
     } else {
 #pragma unroll
       for (int i = 0; i < K_PER_THREAD; ++i) {
         const int u = tid + i * THREADS;
-        const int key = u / CPR, c = u % CPR;
-        kst[i] = __builtin_amdgcn_raw_buffer_load_b128(rk, (key * D + c * 8) * 2, 0, 0);
+        kst[i] = __builtin_amdgcn_raw_buffer_load_b128(rk, ((u / CPR) * D + (u % CPR) * 8) * 2, 0, 0);
       }
 #pragma unroll
       for (int i = 0; i < V_PER_THREAD; ++i) {
         const int u = tid + i * THREADS;
         if (V_UNITS % THREADS == 0 || u < V_UNITS) {
-          const int kg8 = u / CPR, c = u % CPR;
 #pragma unroll
           for (int e = 0; e < 8; ++e)
-            vst[i][e] = __builtin_amdgcn_raw_buffer_load_b128(rv, (v_key(kg8, e) * D + c * 8) * 2, 0, 0);
+            vst[i][e] = __builtin_amdgcn_raw_buffer_load_b128(rv, (v_key(u / CPR, e) * D + (u % CPR) * 8) * 2, 0, 0);
         }
       }
     }
@@ -389,18 +344,15 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
 #pragma unroll
         for (int i = 0; i < K_PER_THREAD; ++i) {
           const int u = (tid - V_UNITS) + i * K_THREADS;
-          if (K_PIECES % K_THREADS == 0 || u < K_PIECES) {
-            const int key = u / CPR, c = u % CPR;
-            *reinterpret_cast<u32x4*>(kb + key * K_ROW + (c << 4)) = stg[i];
-          }
+          if (K_PIECES % K_THREADS == 0 || u < K_PIECES)
+            *reinterpret_cast<u32x4*>(kb + (u / CPR) * K_ROW + ((u % CPR) << 4)) = stg[i];
         }
       }
     } else {
 #pragma unroll
       for (int i = 0; i < K_PER_THREAD; ++i) {
         const int u = tid + i * THREADS;
-        const int key = u / CPR, c = u % CPR;
-        *reinterpret_cast<u32x4*>(kb + key * K_ROW + (c << 4)) = kst[i];
+        *reinterpret_cast<u32x4*>(kb + (u / CPR) * K_ROW + ((u % CPR) << 4)) = kst[i];
       }
 #pragma unroll
       for (int i = 0; i < V_PER_THREAD; ++i) {
@@ -409,6 +361,8 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
       }
     }
     if (MODE == kProfile && tid < BN) {
+      // per-key mask code: the key's frame (spatial) or in-frame position (temporal), or
+      // "kept by every query" (text / sink key, unmasked pass), or "out of range"
       const int key = col * BN + tid;
       int code;
       if (key >= a.N) {
@@ -444,39 +398,20 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
     }
   };
 
-  // Tile cursor.  One query tile per workgroup (QT == 1): a ring holds the current tile
-  // and the next three, so no scalar load sits between one tile's barrier and the next
-  // tile's global loads.  (Reading a line of the tile three steps ahead to warm L2 was
-  // tried and measured slower.)
-  // Several query tiles per workgroup: their lists are merged on the fly (peek / take).
-  int lj = 0, lcol1 = kNoTile, lcol2 = kNoTile, lcol3 = kNoTile;
-  auto next_in_order = [&]() -> int {      // QT == 1: the next tile of this workgroup, any mode
-    if (MODE == kSparse) {
-      const int j = lj++;
-      return j < le[0] ? cols[j] : kNoTile;
-    }
-    return peek();       // dense: counter (take() advances it); profile: generator
-  };
-  int col;
-  if (QT == 1) {
-    lj = li[0];
-    col = next_in_order();
-    if (MODE == kDense) ++jdense;
-    lcol1 = next_in_order();
-    if (MODE == kDense) ++jdense;
-    lcol2 = next_in_order();
-    if (MODE == kDense) ++jdense;
-    lcol3 = next_in_order();
-    if (MODE == kDense) ++jdense;
-  } else {
-    col = peek();
-  }
-  bool mine_cur = false, mine_next = false;
-  if (MODE == kSparse && QT > 1) {
-    mine_cur = col != kNoTile ? take(col) : false;
-    lcol1 = peek();
-    mine_next = lcol1 != kNoTile ? take(lcol1) : false;
-  }
+  // ======================================================================================
+  // Main loop.
+  // ======================================================================================
+  f32x16 oacc[DB];
+#pragma unroll
+  for (int db = 0; db < DB; ++db)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) oacc[db][e] = 0.f;
+  float m_run = kNegBig;   // reference maximum (raw logits, before scaling)
+  float l_run = 0.f;       // this lane's share of the running row sum
+
+  // a ring holds the current tile and the next three, so no scalar load sits between one
+  // tile's barrier and the next tile's global loads
+  int col = next_tile(), col1 = next_tile(), col2 = next_tile(), col3 = next_tile();
   if (col != kNoTile) {
     load_tile(col);
     store_tile(0, col);
@@ -488,9 +423,7 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
   // and emits vmcnt waits in front of the first products of every iteration, which then
   // wait for the NEXT tile's freshly issued global loads instead.
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb)
-#pragma unroll
-    for (int s = 0; s < DS; ++s) asm volatile("" ::"v"(qreg[qb][s]));
+  for (int s = 0; s < DS; ++s) asm volatile("" ::"v"(qreg[s]));
 
   int buf = 0;
   // byte offset of channel d = 32 db + r inside a V^T group row (see store_v_unit)
@@ -504,62 +437,37 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
   const bool ragged = (a.N % BN) != 0;
 
   while (col != kNoTile) {
-    bool mine;
-    int next_col;
-    if (QT == 1) {
-      mine = true;
-      next_col = lcol1;
-      lcol1 = lcol2;
-      lcol2 = lcol3;
-      lcol3 = next_in_order();
-      if (MODE == kDense) ++jdense;
-    } else if (MODE == kSparse) {
-      // merged lists run one step ahead: this tile and the next are already known, the
-      // one after is worked out now (its scalar loads complete during this tile)
-      mine = mine_cur;
-      next_col = lcol1;
-      mine_cur = mine_next;
-      lcol1 = peek();
-      mine_next = lcol1 != kNoTile ? take(lcol1) : false;
-    } else {
-      mine = take(col);
-      next_col = peek();
-    }
+    const int next_col = col1;
+    col1 = col2;
+    col2 = col3;
+    col3 = next_tile();
     if (next_col != kNoTile) load_tile(next_col);
 
     // profile: does this wavefront need the tile at all, and does it need per-element masks?
-    bool need_masks = MODE == kProfile;
+    bool skip = false, need_masks = MODE == kProfile;
     if (MODE == kProfile) {
       const int cmin = tile_info[buf * 4 + 0], cmax = tile_info[buf * 4 + 1], flags = tile_info[buf * 4 + 2];
       bool lane_all = (flags & 6) == 0, lane_none = (flags & 5) == 0;
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        if (cmax >= cmin) {       // the tile has coordinate keys
-          const bool in_lo = (unsigned)(cmin - win_lo[qb]) <= win_span[qb];
-          const bool in_hi = (unsigned)(cmax - win_lo[qb]) <= win_span[qb];
-          lane_all = lane_all && in_lo && in_hi;
-          // disjoint: the whole range lies below or above this row's window
-          const long long lo = win_lo[qb], hi = lo + (long long)win_span[qb];
-          lane_none = lane_none && (cmax < lo || cmin > hi);
-        } else {
-          lane_none = lane_none && (flags & 1) == 0;
-        }
+      if (cmax >= cmin) {       // the tile has coordinate keys
+        const bool in_lo = (unsigned)(cmin - win_lo) <= win_span;
+        const bool in_hi = (unsigned)(cmax - win_lo) <= win_span;
+        lane_all = lane_all && in_lo && in_hi;
+        // disjoint: the whole range lies below or above this row's window
+        const long long lo = win_lo, hi = lo + (long long)win_span;
+        lane_none = lane_none && (cmax < lo || cmin > hi);
       }
-      const bool wave_all = __builtin_amdgcn_ballot_w64(!lane_all) == 0;
-      const bool wave_none = __builtin_amdgcn_ballot_w64(!lane_none) == 0;
-      if (wave_none) mine = false;          // no row of this wavefront keeps any key of the tile
-      need_masks = !wave_all;
+      skip = __builtin_amdgcn_ballot_w64(!lane_none) == 0;   // no row of this wave keeps any key
+      need_masks = __builtin_amdgcn_ballot_w64(!lane_all) != 0;
     }
-    if (mine) {
+
+    if (!skip) {
       const unsigned char* kbuf = lds + buf * STAGE_BYTES;
       const unsigned char* vbuf = kbuf + K_BYTES;
 
-      // ---- S^T = K Q^T : each K operand read from LDS feeds QB products.
-      // Operand reads run PF products ahead of their use (a rolling window of PF operand
-      // registers), so after the first few the LDS latency is hidden behind the MFMAs
-      // instead of being paid at the start of every batch; the scheduling barriers pin
-      // the read / product interleave.
-      constexpr int PF = MODE == kProfile ? 2 : SVG_ATTN_PF;   // (the profile form is short of registers)
+      // ---- S^T = K Q^T.  Operand reads run PF products ahead of their use (a rolling
+      // window of PF operand registers), so after the first few the LDS latency is hidden
+      // behind the MFMAs; the scheduling barriers pin the read / product interleave.
+      constexpr int PF = MODE == kProfile ? 2 : kPrefetch;   // (the profile form is short of registers)
       constexpr int NS = KB * DS;          // operands of the first product, order (kb, s)
       constexpr int NV = KB * 2 * DB;      // operands of the second product, order (kb, kk, db)
       auto k_operand = [&](int i) -> bf16x8 {
@@ -570,7 +478,7 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
         const int kg8 = (i / DB) * 2 + g, db = i % DB;     // i / DB = kb * 2 + kk
         return *reinterpret_cast<const bf16x8*>(vbuf + kg8 * V_ROW + v_off[db]);
       };
-      f32x16 sacc[QB][KB];
+      f32x16 sacc[KB];
       bf16x8 opnd[PF];
 #pragma unroll
       for (int i = 0; i < PF; ++i) opnd[i] = k_operand(i);
@@ -579,14 +487,11 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
         const int kb = i / DS, s = i % DS;
         const bf16x8 ka = opnd[i % PF];
         __builtin_amdgcn_sched_barrier(0);
+        if (s == 0) {
 #pragma unroll
-        for (int qb = 0; qb < QB; ++qb) {
-          if (s == 0) {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) sacc[qb][kb][e] = 0.f;
-          }
-          sacc[qb][kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[qb][s], sacc[qb][kb], 0, 0, 0);
+          for (int e = 0; e < 16; ++e) sacc[kb][e] = 0.f;
         }
+        sacc[kb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ka, qreg[s], sacc[kb], 0, 0, 0);
         // refill the slot just consumed: next K operand, or (at the tail) the first V^T
         // operands, which then arrive while the softmax runs
         if (i + PF < NS) opnd[i % PF] = k_operand(i + PF);
@@ -594,11 +499,9 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
         __builtin_amdgcn_sched_barrier(0);
       }
 
-      bf16x8 pb[QB][KB][2];
-#pragma unroll
-      for (int qb = 0; qb < QB; ++qb) {
-        // ---- masking.  sacc[kb][4 i + jj] belongs to key  col*BN + 32 kb + 8 i + 4 g + jj.
-        if (MODE == kProfile && need_masks) {
+      // ---- masking.  sacc[kb][4 i + jj] belongs to key  col*BN + 32 kb + 8 i + 4 g + jj.
+      if (MODE == kProfile) {
+        if (need_masks) {
 #pragma unroll
           for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
@@ -606,80 +509,79 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
               const i32x4 cc = *reinterpret_cast<const i32x4*>(&key_code[buf * BN + kb * 32 + 8 * i + 4 * g]);
 #pragma unroll
               for (int jj = 0; jj < 4; ++jj) {
-                const bool keep = ((unsigned)(cc[jj] - win_lo[qb]) <= win_span[qb]) || cc[jj] == kCodeKeep;
-                if (!keep) sacc[qb][kb][4 * i + jj] = -INFINITY;
+                const bool keep = ((unsigned)(cc[jj] - win_lo) <= win_span) || cc[jj] == kCodeKeep;
+                if (!keep) sacc[kb][4 * i + jj] = -INFINITY;
               }
             }
-        } else if (MODE != kProfile && ragged && col == a.nk - 1) {
-          int lim = a.N - col * BN - 4 * g;     // keys with 32 kb + 8 i + jj >= lim are out of range
-          // opaque to the optimiser: keeps this rarely taken masking code inside the
-          // branch instead of being speculated into every tile
-          asm volatile("" : "+v"(lim));
-#pragma unroll
-          for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-              for (int jj = 0; jj < 4; ++jj)
-                if (kb * 32 + 8 * i + jj >= lim) sacc[qb][kb][4 * i + jj] = -INFINITY;
         }
-
-        // ---- online softmax: one query per lane.
-        // Fast path: exponentials are taken against the current reference m_run without
-        // looking at the tile's maximum.  That is the same softmax as long as nothing
-        // overflows, which the row sum reveals: if any lane's partial sum exceeds
-        // kLazySum (or is inf / NaN) the whole wave takes the slow path, which finds the
-        // tile maximum, raises the reference, rescales O^T and the running sum, and redoes
-        // the tile's exponentials.  With a reference within 2^13 of the true maximum the
-        // fp32 sums and bf16 weights lose nothing, and almost every tile after the first
-        // few stays on the fast path (no max reduction, no rescale).
-        auto exponentiate = [&](float mc) -> float {
-          float l_loc = 0.f;
+      } else if (ragged && col == a.nk - 1) {
+        int lim = a.N - col * BN - 4 * g;     // keys with 32 kb + 8 i + jj >= lim are out of range
+        // opaque to the optimiser: keeps this rarely taken masking code inside the
+        // branch instead of being speculated into every tile
+        asm volatile("" : "+v"(lim));
 #pragma unroll
-          for (int kb = 0; kb < KB; ++kb)
+        for (int kb = 0; kb < KB; ++kb)
 #pragma unroll
-            for (int kk = 0; kk < 2; ++kk) {
-              f32x8 p;
+          for (int i = 0; i < 4; ++i)
 #pragma unroll
-              for (int e = 0; e < 8; ++e) {
-                p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[qb][kb][8 * kk + e], a.scale_log2, -mc));
-                l_loc += p[e];
-              }
-              pb[qb][kb][kk] = __builtin_convertvector(p, bf16x8);
-            }
-          return l_loc;
-        };
-        float l_loc = exponentiate(m_run[qb] * a.scale_log2);
-        if (__builtin_amdgcn_ballot_w64(!(l_loc <= kLazySum)) != 0) {
-          float m_loc = sacc[qb][0][0];
-#pragma unroll
-          for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) m_loc = fmaxf(m_loc, sacc[qb][kb][e]);
-          m_loc = both_halves_max(m_loc);
-          const float m_new = fmaxf(m_run[qb], m_loc);
-          const float alpha = __builtin_amdgcn_exp2f((m_run[qb] - m_new) * a.scale_log2);
-          m_run[qb] = m_new;
-          l_run[qb] *= alpha;
-#pragma unroll
-          for (int db = 0; db < DB; ++db)
-#pragma unroll
-            for (int e = 0; e < 16; ++e) oacc[qb][db][e] *= alpha;
-          l_loc = exponentiate(m_new * a.scale_log2);
-        }
-        l_run[qb] += l_loc;
+            for (int jj = 0; jj < 4; ++jj)
+              if (kb * 32 + 8 * i + jj >= lim) sacc[kb][4 * i + jj] = -INFINITY;
       }
 
-      // ---- O^T += V^T P^T : each V^T operand read from LDS feeds QB products.  The first
-      // PF operands were requested at the end of the first product (slot (NS + i) % PF).
+      // ---- online softmax: one query per lane.
+      // Fast path: exponentials are taken against the current reference m_run without
+      // looking at the tile's maximum.  That is the same softmax as long as nothing
+      // overflows, which the row sum reveals: if any lane's partial sum exceeds
+      // kLazySum (or is inf / NaN) the whole wave takes the slow path, which finds the
+      // tile maximum, raises the reference, rescales O^T and the running sum, and redoes
+      // the tile's exponentials.  With a reference within 2^13 of the true maximum the
+      // fp32 sums and bf16 weights lose nothing, and almost every tile after the first
+      // few stays on the fast path (no max reduction, no rescale).
+      bf16x8 pb[KB][2];
+      auto exponentiate = [&](float mc) -> float {
+        float l_loc = 0.f;
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+          for (int kk = 0; kk < 2; ++kk) {
+            f32x8 p;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+              p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][8 * kk + e], a.scale_log2, -mc));
+              l_loc += p[e];
+            }
+            pb[kb][kk] = __builtin_convertvector(p, bf16x8);
+          }
+        return l_loc;
+      };
+      float l_loc = exponentiate(m_run * a.scale_log2);
+      if (__builtin_amdgcn_ballot_w64(!(l_loc <= kLazySum)) != 0) {
+        float m_loc = sacc[0][0];
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) m_loc = fmaxf(m_loc, sacc[kb][e]);
+        m_loc = both_halves_max(m_loc);
+        const float m_new = fmaxf(m_run, m_loc);
+        const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * a.scale_log2);
+        m_run = m_new;
+        l_run *= alpha;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+          for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
+        l_loc = exponentiate(m_new * a.scale_log2);
+      }
+      l_run += l_loc;
+
+      // ---- O^T += V^T P^T.  The first PF operands were requested at the end of the first
+      // product (slot (NS + i) % PF).
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
         const int kbkk = i / DB, db = i % DB;
         const bf16x8 va = opnd[(NS + i) % PF];
         __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int qb = 0; qb < QB; ++qb)
-          oacc[qb][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[qb][kbkk >> 1][kbkk & 1], oacc[qb][db], 0, 0, 0);
+        oacc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(va, pb[kbkk >> 1][kbkk & 1], oacc[db], 0, 0, 0);
         if (i + PF < NV) opnd[(NS + i) % PF] = v_operand(i + PF);
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -691,43 +593,39 @@ __global__ __launch_bounds__(64 * NW, (NW >= 4 && QB == 1) ? 2 : 1) void attn_ke
     col = next_col;
   }
 
-  // ---- epilogue: normalise and store.  oacc[db][4 i + jj] = O[query r][32 db + 8 i + 4 g + jj]
+  // ======================================================================================
+  // Epilogue: normalise and store.  oacc[db][4 i + jj] = O[query r][32 db + 8 i + 4 g + jj]
+  // ======================================================================================
+  const float l_tot = both_halves_sum(l_run);
+  const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
+  if (MODE == kProfile) {
+    if (qslot < a.t) {
+      // output slots: [0, nsplit) unmasked key ranges, nsplit spatial, nsplit + 1 temporal
+      const int slot = variant == 0 ? chunk : a.nsplit + variant - 1;
+      float* op = static_cast<float*>(a.o) + (((size_t)slot * a.BH + bh) * a.t + qslot) * D;
+      if (variant == 0 && g == 0) a.stats[((size_t)chunk * a.BH + bh) * a.t + qslot] = make_float2(m_run, l_tot);
 #pragma unroll
-  for (int qb = 0; qb < QB; ++qb) {
-    const float l_tot = both_halves_sum(l_run[qb]);
-    const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
-    if (MODE == kProfile) {
-      if (qslot[qb] < a.t) {
-        // output slots: [0, nsplit) unmasked key ranges, nsplit spatial, nsplit + 1 temporal
-        const int slot = variant == 0 ? chunk : a.nsplit + variant - 1;
-        float* op = static_cast<float*>(a.o) + (((size_t)slot * a.BH + bh) * a.t + qslot[qb]) * D;
-        if (variant == 0 && g == 0) {
-          float2* st = a.stats + ((size_t)chunk * a.BH + bh) * a.t + qslot[qb];
-          *st = make_float2(m_run[qb], l_tot);
+      for (int db = 0; db < DB; ++db)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          f32x4 x;
+#pragma unroll
+          for (int jj = 0; jj < 4; ++jj) x[jj] = oacc[db][4 * i + jj] * inv;
+          *reinterpret_cast<f32x4*>(op + db * 32 + 8 * i + 4 * g) = x;
         }
+    }
+  } else {
+    if (qslot < a.N) {
+      __bf16* op = static_cast<__bf16*>(a.o) + (head + qslot) * D;
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+      for (int db = 0; db < DB; ++db)
 #pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            f32x4 x;
+        for (int i = 0; i < 4; ++i) {
+          f32x4 x;
 #pragma unroll
-            for (int jj = 0; jj < 4; ++jj) x[jj] = oacc[qb][db][4 * i + jj] * inv;
-            *reinterpret_cast<f32x4*>(op + db * 32 + 8 * i + 4 * g) = x;
-          }
-      }
-    } else {
-      if (qslot[qb] < a.N) {
-        __bf16* op = static_cast<__bf16*>(a.o) + (head + qslot[qb]) * D;
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            f32x4 x;
-#pragma unroll
-            for (int jj = 0; jj < 4; ++jj) x[jj] = oacc[qb][db][4 * i + jj] * inv;
-            *reinterpret_cast<bf16x4*>(op + db * 32 + 8 * i + 4 * g) = __builtin_convertvector(x, bf16x4);
-          }
-      }
+          for (int jj = 0; jj < 4; ++jj) x[jj] = oacc[db][4 * i + jj] * inv;
+          *reinterpret_cast<bf16x4*>(op + db * 32 + 8 * i + 4 * g) = __builtin_convertvector(x, bf16x4);
+        }
     }
   }
 }
@@ -844,34 +742,27 @@ __global__ __launch_bounds__(64) void profile_label_kernel(const float2* partial
   labels[bh] = ms < mt ? SVG_HEAD_SPATIAL : SVG_HEAD_TEMPORAL;
 }
 
-#ifndef SVG_ATTN_QB
-#define SVG_ATTN_QB 1     // 32-query blocks per wavefront for the 128x64-tile kernels
-#endif
-#ifndef SVG_ATTN_NW
-#define SVG_ATTN_NW 4     // wavefronts per workgroup for the 128x64-tile kernels (4: one query tile, 8: two; 8 measured slower)
-#endif
-
-template <int D, int NW, int QB, int BN, int MODE>
+// rows_total: N for dense / sparse, t for profiling
+template <int D, int NW, int BN, int MODE>
 int launch_one(AttnArgs a, int rows_total, hipStream_t stream) {
-  constexpr int BMW = 32 * QB * NW;
-  a.nqt = (rows_total + BMW - 1) / BMW;
-  a.total = (MODE == kProfile ? a.nsplit + 2 : 1) * a.BH * a.nqt;
-  const unsigned grid = MODE == kProfile ? (unsigned)(8 * (a.nsplit + 2) * ((a.BH * a.nqt + 7) / 8))
+  constexpr int BM = 32 * NW;
+  a.nqt = (rows_total + BM - 1) / BM;
+  a.total = a.BH * a.nqt;
+  const unsigned grid = MODE == kProfile ? (unsigned)(8 * (a.nsplit + 2) * ((a.total + 7) / 8))
                                          : (unsigned)(((a.total + 7) / 8) * 8);
   (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
-  hipLaunchKernelGGL((attn_kernel<D, NW, QB, BN, MODE>), dim3(grid), dim3(64 * NW), 0, stream, a);
+  hipLaunchKernelGGL((attn_kernel<D, NW, BN, MODE>), dim3(grid), dim3(64 * NW), 0, stream, a);
   return hip_status(hipGetLastError());
 }
 
-// rows_total: N for dense / sparse, t for profiling
 template <int MODE>
 int dispatch(const Geo& g, const AttnArgs& a, int rows_total, hipStream_t stream) {
   if (g.bm == 128) {
-    return g.D == 128 ? launch_one<128, SVG_ATTN_NW, SVG_ATTN_QB, 64, MODE>(a, rows_total, stream)
-                      : launch_one<64, SVG_ATTN_NW, SVG_ATTN_QB, 64, MODE>(a, rows_total, stream);
+    return g.D == 128 ? launch_one<128, 4, 64, MODE>(a, rows_total, stream)
+                      : launch_one<64, 4, 64, MODE>(a, rows_total, stream);
   }
-  return g.D == 128 ? launch_one<128, 1, 1, 32, MODE>(a, rows_total, stream)
-                    : launch_one<64, 1, 1, 32, MODE>(a, rows_total, stream);
+  return g.D == 128 ? launch_one<128, 1, 32, MODE>(a, rows_total, stream)
+                    : launch_one<64, 1, 32, MODE>(a, rows_total, stream);
 }
 
 AttnArgs base_args(const Geo& g, const void* q, const void* k, const void* v, void* o) {
@@ -880,7 +771,7 @@ AttnArgs base_args(const Geo& g, const void* q, const void* k, const void* v, vo
   a.k = static_cast<const __bf16*>(k);
   a.v = static_cast<const __bf16*>(v);
   a.o = o;
-  a.N = g.N; a.nq = g.nq; a.nk = g.nk; a.BH = g.B * g.H;
+  a.N = g.N; a.nk = g.nk; a.BH = g.B * g.H;
   a.scale_log2 = g.scale * 1.4426950408889634f;
   a.off = g.off; a.video_end = g.video_end; a.F = g.F; a.P = g.P;
   a.w_s = g.w_s; a.w_t = g.w_t; a.sink = g.sink;
@@ -918,15 +809,15 @@ int launch_profile(const Geo& g, const void* q, const void* k, const void* v, co
   float2* partial = stats + (size_t)ns * a.BH * t;
   int32_t* order = reinterpret_cast<int32_t*>(partial + (size_t)a.BH * n_partial);
   a.stats = stats;
+  a.order_t = order;
   (void)hipGetLastError();
   hipLaunchKernelGGL(profile_order_kernel, dim3(1), dim3(1024), 0, stream, rows, t, g.off, g.video_end,
                      g.P, order);
   int rc = hip_status(hipGetLastError());
   if (rc != SVG_OK) return rc;
-  a.order_t = order;
   rc = dispatch<kProfile>(g, a, t, stream);
   if (rc != SVG_OK) return rc;
-  (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
+  (void)hipGetLastError();
   hipLaunchKernelGGL(profile_error_kernel, dim3(n_partial, a.BH), dim3(256), 0, stream, workspace, stats,
                      rows, a.BH, t, g.D, ns, a.scale_log2, g.off, g.video_end, partial);
   rc = hip_status(hipGetLastError());

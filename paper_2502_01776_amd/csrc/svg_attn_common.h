@@ -33,20 +33,13 @@ struct AttnArgs {
   int t;                      // profile: number of sampled rows
   int nsplit;                 // profile: key ranges the unmasked pass is cut into
   float2* stats;              // profile: (reference maximum, row sum) per (key range, head, row)
-  int N, nq, nk, BH;
-  int nqt;                    // row groups (workgroups) per head: ceil(nq / tiles per workgroup); profile: ceil(t / rows per workgroup)
+  int N, nk, BH;
+  int nqt;                    // workgroups per head: query tiles (dense, sparse) or ceil(t / rows per workgroup) (profile)
   int reverse_q;              // process query tiles last-to-first (heavy text-suffix tiles first)
   int total;                  // logical workgroups
   float scale_log2;           // softmax scale * log2(e)
   int off, video_end, F, P, w_s, w_t, sink;
 };
-
-template <int D>
-__device__ __forceinline__ int k_swizzle(int key) {
-  // XOR applied to the 16-byte piece index of a K row so that the 16 lanes served
-  // together by a ds_read_b128 hit 16 different 4-bank groups.
-  return D == 128 ? (key & 15) : ((key >> 1) & 7);
-}
 
 // Lanes l and l^32 own the two halves of one query's keys.  v_permlane32_swap with
 // both operands equal returns {x[l % 32], x[32 + l % 32]} in every lane, so the
