@@ -46,6 +46,10 @@ namespace {
 using namespace attn;
 
 constexpr int kNoTile = 0x7fffffff;
+// Wave priority while a wavefront issues a batch of products (0 elsewhere).  The two
+// wavefronts sharing a SIMD then settle into opposite phases: the products of one run
+// back to back while the other's softmax and staging instructions fill the gaps.
+constexpr int kPrioProducts = 1;
 constexpr int kPrefetch = 4;          // LDS operand reads kept in flight ahead of the products
 constexpr unsigned kRsrcFlags = 0x00020000u;   // raw buffer, 32-bit data format (gfx9 encoding)
 
@@ -482,6 +486,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
       bf16x8 opnd[PF];
 #pragma unroll
       for (int i = 0; i < PF; ++i) opnd[i] = k_operand(i);
+      __builtin_amdgcn_s_setprio(kPrioProducts);
 #pragma unroll
       for (int i = 0; i < NS; ++i) {
         const int kb = i / DS, s = i % DS;
@@ -499,6 +504,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
         __builtin_amdgcn_sched_barrier(0);
       }
 
+      __builtin_amdgcn_s_setprio(0);
       // ---- masking.  sacc[kb][4 i + jj] belongs to key  col*BN + 32 kb + 8 i + 4 g + jj.
       if (MODE == kProfile) {
         if (need_masks) {
@@ -576,6 +582,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
 
       // ---- O^T += V^T P^T.  The first PF operands were requested at the end of the first
       // product (slot (NS + i) % PF).
+      __builtin_amdgcn_s_setprio(kPrioProducts);
 #pragma unroll
       for (int i = 0; i < NV; ++i) {
         const int kbkk = i / DB, db = i % DB;
@@ -587,6 +594,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
       }
     }
 
+    __builtin_amdgcn_s_setprio(0);
     if (next_col != kNoTile) store_tile(buf ^ 1, next_col);
     __syncthreads();
     buf ^= 1;

@@ -55,7 +55,6 @@ __device__ __forceinline__ float both_halves_sum(float x) {
   return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-
 }  // namespace attn
 
 }  // namespace svg
