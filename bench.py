@@ -213,11 +213,18 @@ def main():
     tile_flops = 4.0 * cfg["block_m"] * cfg["block_n"] * D
     sparse_ms = breakdown["sparse_attn"]
     achieved = tile_flops * nnz_total / (sparse_ms * 1e-3) / 1e12
-    traffic = None
+    # figures that need hardware counters come from the committed rocprofv3 summary of this
+    # same command (not measured live): bytes past L2 per launch, and the fraction of shader
+    # cycles with the MFMA unit busy together with the shader clock those cycles ran at
+    traffic = counters = None
     tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.workload}.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
-            traffic = json.load(f).get("sparse_attn_bytes_per_launch")
+            prof = json.load(f)
+        traffic = prof.get("sparse_attn_bytes_per_launch")
+        if "sparse_attn_mfma_busy_fraction_of_cycles" in prof:
+            counters = {"mfma_busy_fraction_of_cycles": prof["sparse_attn_mfma_busy_fraction_of_cycles"],
+                        "shader_clock_ghz": prof["sparse_attn_shader_clock_ghz"], "source": prof.get("source")}
     layout_bytes = 2.0 * n_temporal * N * D * 2 + 2.0 * (BH - n_temporal) * N * D * 2   # read + write, all heads
     out = {
         "metric": "effective TFLOP/s of one sparse attention layer at %dk tokens "
@@ -243,7 +250,7 @@ def main():
         "profile_nominal_tflops": 3 * 4.0 * t * N * D * BH / (breakdown["profile"] * 1e-3) / 1e12,
         "roofline": {"kernel": "attn_kernel<128,4,64,sparse>" if D == 128 else "attn_kernel<64,4,64,sparse>",
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic},
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic, "counters": counters},
     }
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, rows_np, labels_np, nnz_total)

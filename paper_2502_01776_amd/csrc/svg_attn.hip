@@ -31,12 +31,19 @@
 // P is rounded to bf16 for the second product; accumulation is fp32; the running sum
 // uses the unrounded P.
 //
-// Measured on MI355X (see the rocprofv3 summaries): plain VALU instructions do not
-// overlap with MFMA execution on a SIMD (only the transcendental unit does), and with
-// 32 query rows per wavefront every MFMA needs a fresh 1 KB operand from LDS, which
-// by itself saturates the 128 B/clk LDS port at MFMA peak.  Wider per-wave tiles (64
-// rows) need more than 256 registers at D = 128 and were slower with the compiler's
-// AGPR handling; an 8-wavefront, two-query-tile workgroup was slower as well.
+// Measured on MI355X:
+//  * With 32 query rows per wavefront every MFMA needs a fresh 1 KB operand from LDS,
+//    which by itself saturates the 128 B/clk LDS port at MFMA peak; together with the
+//    staging writes the LDS is busy about 70 % of the time at the speed reached here.
+//  * A lone wavefront hides only about 12 cycles of other instructions behind each
+//    32-cycle MFMA; two wavefronts on a SIMD overlap one's VALU work with the other's
+//    products much better, and best when each runs long homogeneous phases (products /
+//    softmax) and the one issuing products has the higher wave priority.  Interleaving
+//    softmax slices between the products of the same wavefront was 10 % slower.
+//  * A 64-row-per-wavefront variant (O^T and Q^T in accumulation registers through
+//    hand-written MFMA statements, one wavefront per SIMD, software pipelined) halves the
+//    LDS reads but loses that overlap and came out 8 % slower; an 8-wavefront,
+//    two-query-tile workgroup was slower as well.
 #include "svg_attn_common.h"
 
 namespace svg {
