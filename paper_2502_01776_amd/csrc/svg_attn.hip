@@ -201,12 +201,49 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   // ======================================================================================
   const int32_t* cols = nullptr;
   int lj = 0, lend = 0;              // sparse: cursor and end in col_idx;  dense: counter and nk
+  int lbeg = 0, lleft = 0;           // sparse: start of the list row, entries still to hand out
   if (MODE == kSparse) {
     const int pat = a.labels ? (a.labels[bh] != 0) : 0;
     const int32_t* rp = a.row_ptr[pat];
     cols = a.col_idx[pat];
-    lj = rp[grp];
-    lend = rp[grp + 1];
+    lbeg = __builtin_amdgcn_readfirstlane(rp[grp]);
+    lend = __builtin_amdgcn_readfirstlane(rp[grp + 1]);
+    lj = lbeg;
+    lleft = lend - lbeg;
+    // Where to start in the (cyclically walked) list.  Neighbouring query tiles run at the
+    // same time on one XCD and their key windows overlap but are shifted against each other;
+    // walked from their own first tile they would ask L2 for different tiles at every
+    // moment.  Instead all query tiles of a cohort (cs consecutive ones of a head) start at
+    // one common key tile, the first window tile of the cohort member with the highest
+    // window, wrap around at the end of their list and stop where they started: as long
+    // as they run at the same pace they all want the same K/V tile at the same time.  The
+    // order of the tiles does not change the result beyond fp32 summation order, and a
+    // full list (every member starts at tile 0) is walked exactly like the dense kernel.
+    if (lleft > 1) {
+      const int first_video_tile = (a.off + BN - 1) / BN;      // tiles before it are text-prefix tiles
+      auto holds_text = [&](int gq) { return gq * BM < a.off || (gq + 1) * BM > a.video_end; };
+      const int u = a.reverse_q ? a.nqt - 1 - grp : grp;       // position in dispatch order
+      for (int cs = 64; cs >= 16; cs >>= 2) {
+        const int u0 = u & ~(cs - 1), u1 = min(u0 + cs - 1, a.nqt - 1);
+        // member with the highest window: highest query tile of the cohort that holds no text row
+        int top = a.reverse_q ? a.nqt - 1 - u0 : u1;
+        const int bottom = a.reverse_q ? a.nqt - 1 - u1 : u0;
+        while (top > bottom && holds_text(top)) --top;
+        if (holds_text(top)) break;
+        int anchor = -1;
+        for (int j = rp[top], e = min(rp[top + 1], rp[top] + 8); j < e; ++j)
+          if (cols[j] >= first_video_tile) { anchor = cols[j]; break; }
+        if (anchor < 0) break;
+        // first own entry >= anchor (binary search); usable if the anchor lies inside the own list
+        int lo = 0, hi = lleft;
+        while (lo < hi) {
+          const int mid = (lo + hi) >> 1;
+          if (cols[lbeg + mid] < anchor) lo = mid + 1; else hi = mid;
+        }
+        if (lo < lleft && cols[lbeg + lo] == anchor) { lj = lbeg + lo; break; }
+      }
+      lj = __builtin_amdgcn_readfirstlane(lj);     // (uniform by construction: keeps the cursor scalar)
+    }
   } else if (MODE == kDense) {
     lend = a.nk;
   }
@@ -249,8 +286,11 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   };
   auto next_tile = [&]() -> int {
     if (MODE == kSparse) {
-      const int j = lj++;
-      return j < lend ? cols[j] : kNoTile;
+      if (lleft <= 0) return kNoTile;
+      --lleft;
+      const int c = cols[lj];
+      if (++lj == lend) lj = lbeg;
+      return c;
     }
     if (MODE == kDense) {
       const int j = lj++;

@@ -80,6 +80,25 @@ def test_host_tile_list_sampled_rows_at_full_size(name):
             assert np.array_equal(ci[rp[a]:rp[a + 1]], O.kept_tiles_of_row(g, pattern, a)), (pattern, a)
 
 
+def test_host_tile_counts_match_the_stored_ones():
+    """All six benchmark shapes against tests/golden/tile_counts.txt (counts derived
+    independently of this repository)."""
+    path = os.path.join(ROOT, "tests", "golden", "tile_counts.txt")
+    seen = 0
+    for line in open(path):
+        if not line.strip() or line.startswith("#"):
+            continue
+        name, want_s, want_t, want_all = line.split()
+        cfg = get_config(name)
+        sh = S.shape_from_config(cfg)
+        nq, nk = S.svg_tile_counts(sh)
+        assert nq * nk == int(want_all), name
+        assert len(S.svg_tile_list_build(sh, 0)[1]) == int(want_s), name
+        assert len(S.svg_tile_list_build(sh, 1)[1]) == int(want_t), name
+        seen += 1
+    assert seen == 6
+
+
 def test_tile_list_geometry_variants():
     base = dict(get_config("mid64"), B=1, H=1)
     for F, P, T, tf, ws, wt, bm, bn in [(1, 200, 0, 1, 0, 3, 128, 64), (9, 1, 3, 0, 2, 0, 32, 32),

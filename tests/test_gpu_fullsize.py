@@ -30,7 +30,7 @@ def run_layer(cfg):
     return sh, (q, k, v), rows, labels, mse, (qp, kp, vp, op), o
 
 
-@pytest.mark.parametrize("name", ["cogvideox_v1", "hunyuan_skip85"])
+@pytest.mark.parametrize("name", ["cogvideox_v1", "wan21_14b", "hunyuan", "hunyuan_skip85"])
 def test_full_size_layer_sampled(name):
     cfg = get_config(name)
     g = O.Geometry.from_config(cfg)
@@ -41,7 +41,7 @@ def test_full_size_layer_sampled(name):
 
     # profiling: two heads (one of each label) recomputed by the oracle on a subset of rows
     sub = rows[:: max(1, len(rows) // 96)]
-    for h in (0, 1):
+    for h in (int(np.nonzero(lab == O.SPATIAL)[0][0]), int(np.nonzero(lab == O.TEMPORAL)[0][0])):
         g1 = O.Geometry(**{**g.__dict__, "B": 1, "H": 1})
         omse, olab = O.profile_heads(f64(q[0, h])[None, None], f64(k[0, h])[None, None],
                                      f64(v[0, h])[None, None], sub, g1)
@@ -51,15 +51,18 @@ def test_full_size_layer_sampled(name):
         assert np.allclose(m1.cpu().numpy().reshape(1, 1, 2), omse, rtol=0.05, atol=2e-5)
         assert int(l1[0]) == int(lab[h])
 
-    # layout: head 1 (temporal) bit-exact, head 0 (spatial) untouched
-    assert np.array_equal(bits(qp[0, 1]), O.layout_fwd(bits(q[0, 1]), g))
-    assert np.array_equal(bits(vp[0, 0]), bits(v[0, 0]))
-    assert np.array_equal(bits(o[0, 1]), O.layout_inv(bits(op[0, 1]), g))
+    # layout: a temporal head bit-exact, a spatial head untouched
+    ht = int(np.nonzero(lab == O.TEMPORAL)[0][0])
+    hs = int(np.nonzero(lab == O.SPATIAL)[0][0])
+    assert np.array_equal(bits(qp[0, ht]), O.layout_fwd(bits(q[0, ht]), g))
+    assert np.array_equal(bits(vp[0, hs]), bits(v[0, hs]))
+    assert np.array_equal(bits(o[0, ht]), O.layout_inv(bits(op[0, ht]), g))
 
     # block-sparse attention on sampled query tiles: first, second, frame-straddling,
     # middle, last full, ragged last
     tiles = sorted({0, 1, (g.off + g.P) // g.block_m, nq // 2, nq - 2, nq - 1})
-    for h in (0, 1, g.H - 2, g.H - 1):
+    spatial_heads, temporal_heads = np.nonzero(lab == O.SPATIAL)[0], np.nonzero(lab == O.TEMPORAL)[0]
+    for h in sorted({int(spatial_heads[0]), int(spatial_heads[-1]), int(temporal_heads[0]), int(temporal_heads[-1])}):
         pat = int(lab[h])
         rp = np.zeros(nq + 1, dtype=np.int64)
         cols = []

@@ -106,6 +106,25 @@ def test_empty_tile_rows_give_zeros():
     assert_attn_close(o[0, 0, 256:], ref[256:])
 
 
+def test_sparse_attention_with_first_frame_sink():
+    """Sink flag (Sec. 3.1: the first frame is kept by both patterns): lists from the host builder,
+    both patterns, against the oracle's block-sparse attention over its own lists."""
+    cfg, sh, g = setup("mid128", sink_first_frame=1)
+    q, k, v = make_qkv(cfg)
+    for pat in (O.SPATIAL, O.TEMPORAL):
+        rp, ci = S.svg_tile_list_build(sh, pat)
+        orp, oci = O.tile_list(g, pat)
+        assert np.array_equal(rp, orp) and np.array_equal(ci, oci)
+        o = torch.empty_like(q).cuda()
+        labels = torch.full((g.B * g.H,), pat, dtype=torch.uint8, device="cuda")
+        lists = device_tile_lists(sh)
+        S.svg_sparse_attn_fwd(sh, q.cuda(), k.cuda(), v.cuda(), o, labels, *lists)
+        torch.cuda.synchronize()
+        for h in (0, g.H - 1):
+            ref = O.sparse_attention_head(f64(q)[0, h], f64(k)[0, h], f64(v)[0, h], orp, oci, g)
+            assert_attn_close(o[0, h], ref, f"sink pattern {pat} head {h}")
+
+
 # ------------------------------------------------------------------ profiling
 @pytest.mark.parametrize("name", SMALL)
 def test_profile_heads(name):
@@ -119,6 +138,18 @@ def test_profile_heads(name):
     got = mse.cpu().numpy().astype(np.float64).reshape(g.B, g.H, 2)
     # bf16 rounding of the weights puts a noise floor under the measured errors
     assert np.allclose(got, omse, rtol=0.05, atol=2e-5), (got, omse)
+
+
+@pytest.mark.parametrize("name", ["tiny", "mid64"])
+def test_profile_on_every_row(name):
+    """t = N: the sampled estimate becomes the full comparison of Sec. 3.2."""
+    cfg, sh, g = setup(name)
+    q, k, v = make_qkv(cfg)
+    rows = np.arange(g.N, dtype=np.int32)
+    labels, mse = gpu_profile(sh, q.cuda(), k.cuda(), v.cuda(), rows)
+    omse, olab = O.profile_heads(f64(q), f64(k), f64(v), rows, g)
+    assert labels_match(labels, omse, olab)
+    assert np.allclose(mse.cpu().numpy().reshape(omse.shape), omse, rtol=0.05, atol=2e-5)
 
 
 def test_profile_row_set_spanning_several_query_tiles():
