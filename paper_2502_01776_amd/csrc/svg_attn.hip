@@ -66,6 +66,11 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   constexpr int THREADS = 64 * NW;
   constexpr int CPR = D / 8;             // 16-byte pieces per row
   constexpr int KB = BN / 32;            // 32-key blocks per tile
+  // Tile lists always refer to 64-key tiles.  A kernel whose key tile is 128 keys wide
+  // (head dimension 64: twice the products per barrier) walks the list in pairs: an entry
+  // of the cursor is (128-key tile index) * 4 + (which 64-key halves of it are kept).
+  constexpr int LT = BN == 128 ? 2 : 1;
+  static_assert(LT == 1 || MODE != kProfile, "profiling uses list-sized key tiles");
   constexpr int DS = D / 16;             // k-steps of the first product
   constexpr int DB = D / 32;             // 32-row blocks of O^T
   constexpr int K_PIECES = BN * CPR;
@@ -245,7 +250,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
       lj = __builtin_amdgcn_readfirstlane(lj);     // (uniform by construction: keeps the cursor scalar)
     }
   } else if (MODE == kDense) {
-    lend = a.nk;
+    lend = (a.nk + LT - 1) / LT;
   }
   const int c_lo = MODE == kProfile ? wg_range[0] : 0, c_hi = MODE == kProfile ? wg_range[1] : -1;
   int pseg = 0, pj = 0, pjb = -1;
@@ -290,11 +295,19 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
       --lleft;
       const int c = cols[lj];
       if (++lj == lend) lj = lbeg;
-      return c;
+      if (LT == 1) return c;
+      int halves = 1 << (c & 1);
+      if ((c & 1) == 0 && lleft > 0 && cols[lj] == c + 1) {      // its upper half follows: one full tile
+        halves = 3;
+        --lleft;
+        if (++lj == lend) lj = lbeg;
+      }
+      return (c >> 1) * 4 + halves;
     }
     if (MODE == kDense) {
       const int j = lj++;
-      return j < lend ? j : kNoTile;
+      if (j >= lend) return kNoTile;
+      return LT == 1 ? j : j * 4 + 3;
     }
     while (pj > pjb) {       // profile: move to the next interval that still has tiles
       int k0, k1;
@@ -335,7 +348,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
 
   auto load_tile = [&](int col_any) {
     // the tile index is the same in every lane; saying so keeps the descriptors scalar
-    const int key0 = __builtin_amdgcn_readfirstlane(col_any) * BN;
+    const int key0 = __builtin_amdgcn_readfirstlane(LT == 1 ? col_any : col_any >> 2) * BN;
     const unsigned bytes_left = (unsigned)(a.N - key0) * (D * 2);
     const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<__bf16*>(kh + (size_t)key0 * D), 0, bytes_left, kRsrcFlags);
@@ -493,6 +506,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     col2 = col3;
     col3 = next_tile();
     if (next_col != kNoTile) load_tile(next_col);
+    const int tile = LT == 1 ? col : col >> 2;          // key tile of this iteration, BN keys wide
+    const int halves = LT == 1 ? 3 : (col & 3);
 
     // profile: does this wavefront need the tile at all, and does it need per-element masks?
     bool skip = false, need_masks = MODE == kProfile;
@@ -518,7 +533,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
       // ---- S^T = K Q^T.  Operand reads run PF products ahead of their use (a rolling
       // window of PF operand registers), so after the first few the LDS latency is hidden
       // behind the MFMAs; the scheduling barriers pin the read / product interleave.
-      constexpr int PF = MODE == kProfile ? 2 : kPrefetch;   // (the profile form is short of registers)
+      constexpr int PF = (MODE == kProfile || BN == 128) ? 2 : kPrefetch;   // (those forms are short of registers)
       constexpr int NS = KB * DS;          // operands of the first product, order (kb, s)
       constexpr int NV = KB * 2 * DB;      // operands of the second product, order (kb, kk, db)
       auto k_operand = [&](int i) -> bf16x8 {
@@ -567,8 +582,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
               }
             }
         }
-      } else if (ragged && col == a.nk - 1) {
-        int lim = a.N - col * BN - 4 * g;     // keys with 32 kb + 8 i + jj >= lim are out of range
+      } else if (ragged && (tile + 1) * BN > a.N) {
+        int lim = a.N - tile * BN - 4 * g;     // keys with 32 kb + 8 i + jj >= lim are out of range
         // opaque to the optimiser: keeps this rarely taken masking code inside the
         // branch instead of being speculated into every tile
         asm volatile("" : "+v"(lim));
@@ -579,6 +594,16 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
 #pragma unroll
             for (int jj = 0; jj < 4; ++jj)
               if (kb * 32 + 8 * i + jj >= lim) sacc[kb][4 * i + jj] = -INFINITY;
+      }
+      if (LT == 2 && halves != 3) {
+        // only one 64-key half of this tile is on the list: the other takes no part
+        int hv = halves;
+        asm volatile("" : "+v"(hv));      // (keeps the selects below inside this branch)
+#pragma unroll
+        for (int kb = 0; kb < KB; ++kb)
+#pragma unroll
+          for (int e = 0; e < 16; ++e)
+            if (((hv >> (kb >> 1)) & 1) == 0) sacc[kb][e] = -INFINITY;
       }
 
       // ---- online softmax: one query per lane.
@@ -813,8 +838,11 @@ int launch_one(AttnArgs a, int rows_total, hipStream_t stream) {
 template <int MODE>
 int dispatch(const Geo& g, const AttnArgs& a, int rows_total, hipStream_t stream) {
   if (g.bm == 128) {
-    return g.D == 128 ? launch_one<128, 4, 64, MODE>(a, rows_total, stream)
-                      : launch_one<64, 4, 64, MODE>(a, rows_total, stream);
+    if (g.D == 128) return launch_one<128, 4, 64, MODE>(a, rows_total, stream);
+    // head dimension 64: half the products per key, so the dense and sparse passes take
+    // 128 keys per barrier (the tile list still counts 64-key tiles)
+    if constexpr (MODE == kProfile) return launch_one<64, 4, 64, MODE>(a, rows_total, stream);
+    else return launch_one<64, 4, 128, MODE>(a, rows_total, stream);
   }
   return g.D == 128 ? launch_one<128, 1, 32, MODE>(a, rows_total, stream)
                     : launch_one<64, 1, 32, MODE>(a, rows_total, stream);
