@@ -57,6 +57,7 @@ constexpr int kNoTile = 0x7fffffff;
 // wavefronts sharing a SIMD then settle into opposite phases: the products of one run
 // back to back while the other's softmax and staging instructions fill the gaps.
 constexpr int kPrioProducts = 1;
+constexpr int kCohort = 64;   // consecutive query tiles that share an XCD (and its L2) at a time
 constexpr int kPrefetch = 4;          // LDS operand reads kept in flight ahead of the products
 constexpr unsigned kRsrcFlags = 0x00020000u;   // raw buffer, 32-bit data format (gfx9 encoding)
 
@@ -111,7 +112,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   // stream the same K/V share one L2.
   // ======================================================================================
   const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
-  int bh, grp, variant = 0, chunk = 0;
+  int bh, grp, variant = 0, chunk = 0, lid = 0;
   if (MODE == kProfile) {
     // (head, row group) pairs are split into 8 contiguous chunks, one per XCD.  Each pair
     // has nsplit + 2 units of similar length: the unmasked pass cut into nsplit key
@@ -128,7 +129,18 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     bh = pair / a.nqt;
     grp = pair - bh * a.nqt;
   } else {
-    const int lid = xcd * ((a.total + 7) >> 3) + loc;
+    if (MODE == kDense) {
+      // Dense: blocks of kCohort consecutive logical ids go to one XCD, consecutive blocks to
+      // consecutive XCDs.  An XCD's L2 serves neighbouring query tiles of one head, and at
+      // any time all XCDs work on the same one or two heads, whose K/V (61 MB per head at
+      // the 120k-token shape) then stay in the memory-side cache in front of HBM; with one
+      // head per XCD the dense pass runs into the HBM bandwidth (-11 % time).
+      lid = ((loc / kCohort) * 8 + xcd) * kCohort + (loc % kCohort);
+    } else {
+      // Sparse: one contiguous chunk of logical ids per XCD, so that consecutive cohorts,
+      // whose key windows overlap, find each other's K/V tiles in the same L2.
+      lid = xcd * ((a.total + 7) >> 3) + loc;
+    }
     if (lid >= a.total) return;
     bh = lid / a.nqt;
     grp = lid - bh * a.nqt;
@@ -227,9 +239,11 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     if (lleft > 1) {
       const int first_video_tile = (a.off + BN - 1) / BN;      // tiles before it are text-prefix tiles
       auto holds_text = [&](int gq) { return gq * BM < a.off || (gq + 1) * BM > a.video_end; };
-      const int u = a.reverse_q ? a.nqt - 1 - grp : grp;       // position in dispatch order
-      for (int cs = 64; cs >= 16; cs >>= 2) {
-        const int u0 = u & ~(cs - 1), u1 = min(u0 + cs - 1, a.nqt - 1);
+      // cohort: the logical ids of the same aligned block of cs, as far as they belong to this
+      // head; u = position of a query tile in the head's dispatch order
+      for (int cs = kCohort; cs >= 16; cs >>= 2) {
+        const int u0 = max(lid & ~(cs - 1), bh * a.nqt) - bh * a.nqt;
+        const int u1 = min(lid | (cs - 1), (bh + 1) * a.nqt - 1) - bh * a.nqt;
         // member with the highest window: highest query tile of the cohort that holds no text row
         int top = a.reverse_q ? a.nqt - 1 - u0 : u1;
         const int bottom = a.reverse_q ? a.nqt - 1 - u1 : u0;
@@ -289,11 +303,18 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     }
     return true;
   };
+  // The list entry fetched at the top of a tile is needed three tiles later.  It is loaded
+  // as an ordinary per-lane value (the opaque zero keeps the compiler from treating the
+  // address as uniform and waiting for the load on the spot, which would also wait for
+  // every staging load in flight) and is made scalar late in the iteration, where the
+  // staged data has just been waited for anyway.
+  int lane_zero = 0;
+  asm volatile("" : "+v"(lane_zero));
   auto next_tile = [&]() -> int {
     if (MODE == kSparse) {
       if (lleft <= 0) return kNoTile;
       --lleft;
-      const int c = cols[lj];
+      const int c = cols[lj + (LT == 1 ? lane_zero : 0)];
       if (++lj == lend) lj = lbeg;
       if (LT == 1) return c;
       int halves = 1 << (c & 1);
@@ -475,7 +496,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
 
   // a ring holds the current tile and the next three, so no scalar load sits between one
   // tile's barrier and the next tile's global loads
-  int col = next_tile(), col1 = next_tile(), col2 = next_tile(), col3 = next_tile();
+  int col = __builtin_amdgcn_readfirstlane(next_tile()), col1 = __builtin_amdgcn_readfirstlane(next_tile()),
+      col2 = __builtin_amdgcn_readfirstlane(next_tile()), col3 = __builtin_amdgcn_readfirstlane(next_tile());
   if (col != kNoTile) {
     load_tile(col);
     store_tile(0, col);
@@ -504,7 +526,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     const int next_col = col1;
     col1 = col2;
     col2 = col3;
-    col3 = next_tile();
+    const int col3_pending = next_tile();
     if (next_col != kNoTile) load_tile(next_col);
     const int tile = LT == 1 ? col : col >> 2;          // key tile of this iteration, BN keys wide
     const int halves = LT == 1 ? 3 : (col & 3);
@@ -582,7 +604,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
               }
             }
         }
-      } else if (ragged && (tile + 1) * BN > a.N) {
+      } else if (ragged && (LT == 1 ? col == a.nk - 1 : (tile + 1) * BN > a.N)) {
         int lim = a.N - tile * BN - 4 * g;     // keys with 32 kb + 8 i + jj >= lim are out of range
         // opaque to the optimiser: keeps this rarely taken masking code inside the
         // branch instead of being speculated into every tile
@@ -668,6 +690,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
 
     __builtin_amdgcn_s_setprio(0);
     if (next_col != kNoTile) store_tile(buf ^ 1, next_col);
+    col3 = __builtin_amdgcn_readfirstlane(col3_pending);
     __syncthreads();
     buf ^= 1;
     col = next_col;
@@ -828,8 +851,9 @@ int launch_one(AttnArgs a, int rows_total, hipStream_t stream) {
   constexpr int BM = 32 * NW;
   a.nqt = (rows_total + BM - 1) / BM;
   a.total = a.BH * a.nqt;
-  const unsigned grid = MODE == kProfile ? (unsigned)(8 * (a.nsplit + 2) * ((a.total + 7) / 8))
-                                         : (unsigned)(((a.total + 7) / 8) * 8);
+  const unsigned per_xcd = MODE == kDense ? (unsigned)((a.total + 8 * kCohort - 1) / (8 * kCohort)) * kCohort
+                                          : (unsigned)((a.total + 7) / 8);
+  const unsigned grid = MODE == kProfile ? (unsigned)(8 * (a.nsplit + 2) * ((a.total + 7) / 8)) : 8u * per_xcd;
   (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
   hipLaunchKernelGGL((attn_kernel<D, NW, BN, MODE>), dim3(grid), dim3(64 * NW), 0, stream, a);
   return hip_status(hipGetLastError());
