@@ -303,27 +303,41 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     }
     return true;
   };
-  // The list entry fetched at the top of a tile is needed three tiles later.  It is loaded
-  // as an ordinary per-lane value (the opaque zero keeps the compiler from treating the
-  // address as uniform and waiting for the load on the spot, which would also wait for
-  // every staging load in flight) and is made scalar late in the iteration, where the
-  // staged data has just been waited for anyway.
+  // The cursor works in two halves.  fetch_begin() at the top of an iteration issues the
+  // loads of the next list entries; fetch_end() late in the iteration, where the staged data
+  // has just been waited for anyway, turns them into the next entry and advances the
+  // cursor.  The entry is needed three tiles later.  The loads are ordinary per-lane loads
+  // (the opaque zero keeps the compiler from treating the address as uniform and waiting
+  // for the value on the spot, which would also wait for every staging load in flight).
   int lane_zero = 0;
   asm volatile("" : "+v"(lane_zero));
-  auto next_tile = [&]() -> int {
+  int pend0 = kNoTile, pend1 = kNoTile;
+  auto fetch_begin = [&]() {
+    if (MODE == kSparse) {
+      pend0 = lleft > 0 ? cols[lj + lane_zero] : kNoTile;
+      if (LT == 2) {      // the entry after it: may be the upper half of the same 128-key tile
+        const int lj1 = lj + 1 == lend ? lbeg : lj + 1;
+        pend1 = lleft > 1 ? cols[lj1 + lane_zero] : kNoTile;
+      }
+    }
+  };
+  auto fetch_end = [&]() -> int {
     if (MODE == kSparse) {
       if (lleft <= 0) return kNoTile;
-      --lleft;
-      const int c = cols[lj + (LT == 1 ? lane_zero : 0)];
-      if (++lj == lend) lj = lbeg;
-      if (LT == 1) return c;
-      int halves = 1 << (c & 1);
-      if ((c & 1) == 0 && lleft > 0 && cols[lj] == c + 1) {      // its upper half follows: one full tile
-        halves = 3;
-        --lleft;
-        if (++lj == lend) lj = lbeg;
+      const int c = __builtin_amdgcn_readfirstlane(pend0);
+      int taken = 1, entry = c;
+      if (LT == 2) {
+        int halves = 1 << (c & 1);
+        if ((c & 1) == 0 && lleft > 1 && __builtin_amdgcn_readfirstlane(pend1) == c + 1) {
+          halves = 3;       // its upper half follows: one full tile
+          taken = 2;
+        }
+        entry = (c >> 1) * 4 + halves;
       }
-      return (c >> 1) * 4 + halves;
+      lleft -= taken;
+      lj += taken;
+      if (lj >= lend) lj -= lend - lbeg;
+      return entry;
     }
     if (MODE == kDense) {
       const int j = lj++;
@@ -341,6 +355,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
       pjb = jb;
     }
     return pj++;
+  };
+  auto next_tile = [&]() -> int {      // both halves at once (prologue)
+    fetch_begin();
+    return fetch_end();
   };
 
   // ======================================================================================
@@ -496,8 +514,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
 
   // a ring holds the current tile and the next three, so no scalar load sits between one
   // tile's barrier and the next tile's global loads
-  int col = __builtin_amdgcn_readfirstlane(next_tile()), col1 = __builtin_amdgcn_readfirstlane(next_tile()),
-      col2 = __builtin_amdgcn_readfirstlane(next_tile()), col3 = __builtin_amdgcn_readfirstlane(next_tile());
+  int col = next_tile(), col1 = next_tile(), col2 = next_tile(), col3 = next_tile();
   if (col != kNoTile) {
     load_tile(col);
     store_tile(0, col);
@@ -526,7 +543,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     const int next_col = col1;
     col1 = col2;
     col2 = col3;
-    const int col3_pending = next_tile();
+    fetch_begin();
     if (next_col != kNoTile) load_tile(next_col);
     const int tile = LT == 1 ? col : col >> 2;          // key tile of this iteration, BN keys wide
     const int halves = LT == 1 ? 3 : (col & 3);
@@ -690,7 +707,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
 
     __builtin_amdgcn_s_setprio(0);
     if (next_col != kNoTile) store_tile(buf ^ 1, next_col);
-    col3 = __builtin_amdgcn_readfirstlane(col3_pending);
+    col3 = fetch_end();
     __syncthreads();
     buf ^= 1;
     col = next_col;
