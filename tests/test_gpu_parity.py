@@ -106,6 +106,44 @@ def test_empty_tile_rows_give_zeros():
     assert_attn_close(o[0, 0, 256:], ref[256:])
 
 
+@pytest.mark.parametrize("name", ["mid64", "mid128"])
+def test_sparse_attention_arbitrary_tile_lists(name):
+    """Lists that follow no window structure: random subsets of the key tiles per query tile
+    (lone 64-key halves, gaps, an empty row), different for the two patterns."""
+    cfg, sh, g = setup(name)
+    q, k, v = make_qkv(cfg)
+    nq, nk = O.n_tiles(g)
+    rng = np.random.default_rng(77)
+    lists = []
+    for pat in (0, 1):
+        rp = np.zeros(nq + 1, dtype=np.int32)
+        cols = []
+        for a in range(nq):
+            keep = rng.random(nk) < (0.5 if pat == 0 else 0.25)
+            if a == 1 and pat == 1:
+                keep[:] = False               # an empty row: output zeros
+            elif not keep.any():
+                keep[rng.integers(nk)] = True
+            c = np.nonzero(keep)[0].astype(np.int32)
+            cols.append(c)
+            rp[a + 1] = rp[a] + len(c)
+        lists.append((rp, np.concatenate(cols)))
+    labels = torch.tensor([h & 1 for h in range(g.B * g.H)], dtype=torch.uint8, device="cuda")
+    o = torch.empty_like(q).cuda()
+    S.svg_sparse_attn_fwd(sh, q.cuda(), k.cuda(), v.cuda(), o, labels, dev_i32(lists[0][0]), dev_i32(lists[0][1]),
+                          dev_i32(lists[1][0]), dev_i32(lists[1][1]))
+    torch.cuda.synchronize()
+    for b in range(g.B):
+        for h in range(g.H):
+            rp, ci = lists[(b * g.H + h) & 1]
+            filled = [a for a in range(nq) if rp[a + 1] > rp[a]]
+            ref = O.sparse_attention_head(f64(q)[b, h], f64(k)[b, h], f64(v)[b, h], rp, ci, g, q_tiles=filled)
+            ok = ~np.isnan(ref[:, 0])
+            assert_attn_close(o[b, h][torch.from_numpy(ok).cuda()], ref[ok], f"{name} b{b} h{h}")
+    flat = o.reshape(g.B * g.H, g.N, g.D)
+    assert (flat[1::2, g.block_m:2 * g.block_m] == 0).all()
+
+
 def test_sparse_attention_with_first_frame_sink():
     """Sink flag (Sec. 3.1: the first frame is kept by both patterns): lists from the host builder,
     both patterns, against the oracle's block-sparse attention over its own lists."""
