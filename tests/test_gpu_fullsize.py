@@ -30,7 +30,8 @@ def run_layer(cfg):
     return sh, (q, k, v), rows, labels, mse, (qp, kp, vp, op), o
 
 
-@pytest.mark.parametrize("name", ["cogvideox_v1", "wan21_14b", "hunyuan", "hunyuan_skip85"])
+@pytest.mark.parametrize("name", ["cogvideox_v1", "wan21_14b", "cogvideox_v15", "hunyuan", "hunyuan_skip85",
+                                  "hunyuan_keep31"])
 def test_full_size_layer_sampled(name):
     cfg = get_config(name)
     g = O.Geometry.from_config(cfg)
@@ -88,15 +89,18 @@ def test_full_size_layer_sampled(name):
             assert np.array_equal(bits(o[0, h]), bits(op[0, h]))
 
 
-def test_full_size_dense_sampled_rows():
-    cfg = get_config("cogvideox_v1")
+@pytest.mark.parametrize("name", ["cogvideox_v1", "hunyuan_skip85"])
+def test_full_size_dense_sampled_rows(name):
+    cfg = get_config(name)
     g = O.Geometry.from_config(cfg)
     sh = S.shape_from_config(cfg)
     q, k, v = make_qkv(cfg, device="cuda")
     o = torch.empty_like(q)
     S.svg_dense_attn_fwd(sh, q, k, v, o)
     torch.cuda.synchronize()
-    rows = np.array([0, 1, 127, 128, 225, 226, 5000, 17775 - 128, 17775])
-    for h in (0, 47):
+    # first rows, tile edges, both sides of the text boundary, a middle row, the ragged end
+    edge = g.T if g.text_first else g.F * g.P
+    rows = np.array(sorted({0, 1, 127, 128, edge - 1, edge, 5000, g.N - 129, g.N - 1}))
+    for h in (0, g.H - 1):
         ref = O.dense_attention_head(f64(q[0, h]), f64(k[0, h]), f64(v[0, h]), g, rows=rows)
-        assert_attn_close(o[0, h][rows], ref, f"dense head {h}")
+        assert_attn_close(o[0, h][rows], ref, f"{name} dense head {h}")
