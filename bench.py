@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--dense-reps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--without-layout-transform", action="store_true",
+                    help="also time the comparison arm of Sec. 5.5: temporal heads left in frame-major order "
+                         "with the frame-major temporal tile list (no layout kernels)")
     ap.add_argument("--only", default="", help="time a single stage only (profile|layout|sparse|dense); "
                     "used for per-kernel rocprofv3 runs")
     return ap.parse_args()
@@ -252,6 +255,28 @@ def main():
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic, "counters": counters},
     }
+    if args.without_layout_transform:
+        # same labels, same kernel, unpermuted q, k, v: the temporal slot gets the list of the
+        # temporal mask in frame-major order
+        rp2, ci2 = S.svg_tile_list_build(sh, S.SVG_LIST_TEMPORAL_FRAME_MAJOR)
+        lists2 = lists[:2] + [torch.from_numpy(rp2).cuda(), torch.from_numpy(ci2).cuda()]
+        for _ in range(2):
+            S.svg_sparse_attn_fwd(sh, q, k, v, op, labels, *lists2)
+        torch.cuda.synchronize()
+        e0, e1 = ev(), ev()
+        e0.record()
+        for _ in range(args.steps):
+            S.svg_sparse_attn_fwd(sh, q, k, v, op, labels, *lists2)
+        e1.record()
+        torch.cuda.synchronize()
+        ms2 = e0.elapsed_time(e1) / args.steps
+        nnz2 = (BH - n_temporal) * nnz[0] + n_temporal * int(rp2[-1])
+        out["without_layout_transform"] = {
+            "temporal_tiles_per_head": int(rp2[-1]), "temporal_tiles_per_head_transformed": nnz[1],
+            "kept_tile_fraction": nnz2 / (BH * nq * nk), "sparse_attn_ms": ms2,
+            "ms_per_layer": breakdown["profile"] + ms2,
+            "with_transform_ms_per_layer": wall_ms,
+            "speedup_from_transform": (breakdown["profile"] + ms2) / wall_ms}
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, rows_np, labels_np, nnz_total)
     print(json.dumps(out))

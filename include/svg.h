@@ -46,6 +46,12 @@ typedef struct svg_shape {
 } svg_shape_t;
 
 enum { SVG_HEAD_SPATIAL = 0, SVG_HEAD_TEMPORAL = 1 };
+/* A third list pattern for svg_tile_list_build only (never a head label): the temporal
+ * mask for a head LEFT in frame-major order, i.e. without the layout transformation.  It
+ * exists for the comparison of Sec. 5.5 / Fig. 7 (sparse attention with and without the
+ * transformation): in frame-major order the kept keys of a query tile are one short run
+ * per frame, so many more tiles hold at least one of them. */
+enum { SVG_LIST_TEMPORAL_FRAME_MAJOR = 2 };
 
 typedef enum svg_status {
   SVG_OK = 0,
@@ -78,7 +84,8 @@ int svg_tile_counts(const svg_shape_t* shape, int32_t* nq, int32_t* nk);
 /*
  * Kept-tile list of one pattern (Fig. 4; Sec. 4.3 "block sparse attention").
  * HOST function, pure in its arguments.  pattern is SVG_HEAD_SPATIAL (rows and
- * columns in F-outer order) or SVG_HEAD_TEMPORAL (P-outer order).  Tile (a,b)
+ * columns in F-outer order), SVG_HEAD_TEMPORAL (P-outer order) or
+ * SVG_LIST_TEMPORAL_FRAME_MAJOR (temporal mask, F-outer order).  Tile (a,b)
  * covers rows [a*block_m, min(N,(a+1)*block_m)) and columns
  * [b*block_n, min(N,(b+1)*block_n)) and is kept iff at least one (query, key)
  * pair inside it is kept by the pattern's element mask: either token is text, or

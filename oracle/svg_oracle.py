@@ -36,6 +36,7 @@ import numpy as np
 
 SPATIAL = 0   # Alg. 1: best_mask_config is true for the spatial pattern
 TEMPORAL = 1
+TEMPORAL_FRAME_MAJOR = 2   # tile lists only: the temporal mask for a head left in F-outer order (Sec. 5.5 comparison)
 
 
 @dataclass(frozen=True)
@@ -173,6 +174,8 @@ def kept_tiles_of_row(g: Geometry, pattern: int, a: int) -> np.ndarray:
     r = np.arange(a * g.block_m, min(g.N, (a + 1) * g.block_m))
     if pattern == SPATIAL:
         m = spatial_mask(g, r)
+    elif pattern == TEMPORAL_FRAME_MAJOR:
+        m = temporal_mask(g, r)                    # rows and columns stay in F-outer order
     else:
         inv = np.empty(g.N, dtype=np.int64)
         inv[layout_perm(g)] = np.arange(g.N)       # inv[n'] = original index

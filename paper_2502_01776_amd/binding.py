@@ -17,6 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libsvg_gfx950.so")
 
 SVG_HEAD_SPATIAL = 0
 SVG_HEAD_TEMPORAL = 1
+SVG_LIST_TEMPORAL_FRAME_MAJOR = 2   # list pattern only: temporal mask without the layout transformation
 SVG_OK = 0
 
 EXPORTS = ("svg_strerror", "svg_version", "svg_last_hip_error", "svg_workspace_bytes", "svg_tile_counts",

@@ -85,8 +85,10 @@ int svg_tile_list_build(const svg_shape_t* shape, int pattern, int32_t* row_ptr,
   Geo g;
   int rc = svg::make_geo(shape, &g);
   if (rc != SVG_OK) return rc;
-  if (pattern != SVG_HEAD_SPATIAL && pattern != SVG_HEAD_TEMPORAL) return SVG_ERR_INVALID_ARG;
+  if (pattern != SVG_HEAD_SPATIAL && pattern != SVG_HEAD_TEMPORAL && pattern != SVG_LIST_TEMPORAL_FRAME_MAJOR)
+    return SVG_ERR_INVALID_ARG;
   if (!row_ptr || !nnz_out || (col_idx && cap < 0)) return SVG_ERR_INVALID_ARG;
+  const bool frame_major_temporal = pattern == SVG_LIST_TEMPORAL_FRAME_MAJOR;
 
   // In its own order a pattern groups `unit` consecutive video rows: a frame (P rows)
   // for spatial, a position (F rows) for temporal; `groups` of them; window w groups.
@@ -106,7 +108,7 @@ int svg_tile_list_build(const svg_shape_t* shape, int pattern, int32_t* row_ptr,
     if (g.text_first) mark(always, 0, g.T - 1); else mark(always, v1, g.N - 1);
   }
   if (g.sink) {
-    if (pattern == SVG_HEAD_SPATIAL) {
+    if (pattern == SVG_HEAD_SPATIAL || frame_major_temporal) {
       mark(always, v0, v0 + g.P - 1);
     } else {
       for (int b = 0; b < g.nk; ++b) {  // P-outer: frame-0 tokens sit at video offsets k*F
@@ -126,6 +128,26 @@ int svg_tile_list_build(const svg_shape_t* shape, int pattern, int32_t* row_ptr,
     const bool has_text_query = g.T > 0 && (r0 < v0 || r1 >= v1);
     if (has_text_query) {
       std::fill(keep.begin(), keep.end(), (uint8_t)1);
+    } else if (frame_major_temporal) {
+      // Rows r0..r1 in F-outer order cover the in-frame positions [pa, pb] of one frame, or
+      // wrap over a frame end ([pa, P) and [0, pb]), or every position; each position
+      // interval keeps, in EVERY frame, the keys within w_t positions of it.
+      keep = always;
+      const int64_t pa = (r0 - v0) % g.P, pb = (r1 - v0) % g.P;
+      const bool one_frame = (r0 - v0) / g.P == (r1 - v0) / g.P;
+      auto keep_positions = [&](int64_t lo, int64_t hi) {
+        lo = std::max<int64_t>(0, lo - g.w_t);
+        hi = std::min<int64_t>(g.P - 1, hi + g.w_t);
+        for (int f = 0; f < g.F; ++f) mark(keep, v0 + (int64_t)f * g.P + lo, v0 + (int64_t)f * g.P + hi);
+      };
+      if (one_frame) {
+        keep_positions(pa, pb);
+      } else if (r1 - r0 + 1 >= g.P) {
+        keep_positions(0, g.P - 1);
+      } else {
+        keep_positions(pa, g.P - 1);
+        keep_positions(0, pb);
+      }
     } else {
       keep = always;
       const int64_t ga = (r0 - v0) / unit, gb = (r1 - v0) / unit;

@@ -54,7 +54,7 @@ CASES = ["tiny", "mid64", "mid128", "cogvideox_v1"]
 
 
 @pytest.mark.parametrize("name", CASES)
-@pytest.mark.parametrize("pattern", [0, 1])
+@pytest.mark.parametrize("pattern", [0, 1, 2])
 @pytest.mark.parametrize("sink", [0, 1])
 def test_host_tile_list_is_bit_exact(name, pattern, sink):
     if name == "cogvideox_v1" and sink:
@@ -73,7 +73,7 @@ def test_host_tile_list_sampled_rows_at_full_size(name):
     sh, g = S.shape_from_config(cfg), O.Geometry.from_config(cfg)
     nq, nk = S.svg_tile_counts(sh)
     assert (nq, nk) == O.n_tiles(g)
-    for pattern in (0, 1):
+    for pattern in (0, 1, 2):
         rp, ci = S.svg_tile_list_build(sh, pattern)
         assert rp[0] == 0 and rp[-1] == len(ci) and (np.diff(rp) > 0).all()
         for a in (0, 1, nq // 3, nq // 2, nq - 2, nq - 1):
@@ -125,7 +125,7 @@ def test_tile_list_capacity_and_size_query():
     small = np.zeros(3, np.int32)
     assert lib.svg_tile_list_build(C.byref(sh), 0, rp.ctypes.data, small.ctypes.data, 3, C.byref(nnz)) == -1
     assert nnz.value == rp[-1]
-    assert lib.svg_tile_list_build(C.byref(sh), 2, rp.ctypes.data, None, 0, C.byref(nnz)) == -1
+    assert lib.svg_tile_list_build(C.byref(sh), 3, rp.ctypes.data, None, 0, C.byref(nnz)) == -1
     assert lib.svg_tile_list_build(C.byref(sh), 0, None, None, 0, C.byref(nnz)) == -1
 
 

@@ -144,6 +144,23 @@ def test_sparse_attention_arbitrary_tile_lists(name):
     assert (flat[1::2, g.block_m:2 * g.block_m] == 0).all()
 
 
+def test_sparse_attention_without_layout_transformation():
+    """Temporal heads left in frame-major order with the frame-major temporal list (the
+    comparison arm of Sec. 5.5): same kernel, unpermuted inputs, more tiles."""
+    cfg, sh, g = setup("mid128")
+    q, k, v = make_qkv(cfg)
+    rp, ci = S.svg_tile_list_build(sh, S.SVG_LIST_TEMPORAL_FRAME_MAJOR)
+    orp, oci = O.tile_list(g, O.TEMPORAL_FRAME_MAJOR)
+    assert np.array_equal(rp, orp) and np.array_equal(ci, oci)
+    assert len(ci) > len(S.svg_tile_list_build(sh, S.SVG_HEAD_TEMPORAL)[1])
+    o = torch.empty_like(q).cuda()
+    S.svg_sparse_attn_fwd(sh, q.cuda(), k.cuda(), v.cuda(), o, None, dev_i32(rp), dev_i32(ci), None, None)
+    torch.cuda.synchronize()
+    for h in (1, g.H - 1):
+        ref = O.sparse_attention_head(f64(q)[0, h], f64(k)[0, h], f64(v)[0, h], orp, oci, g)
+        assert_attn_close(o[0, h], ref, f"frame-major temporal head {h}")
+
+
 def test_sparse_attention_with_first_frame_sink():
     """Sink flag (Sec. 3.1: the first frame is kept by both patterns): lists from the host builder,
     both patterns, against the oracle's block-sparse attention over its own lists."""

@@ -464,3 +464,26 @@ def test_tile_counts_match_the_independently_derived_ones(name):
     assert nq * nk == want_all
     assert sum(len(O.kept_tiles_of_row(g, O.SPATIAL, a)) for a in range(nq)) == want_s
     assert sum(len(O.kept_tiles_of_row(g, O.TEMPORAL, a)) for a in range(nq)) == want_t
+
+
+@pytest.mark.parametrize("name", ["tiny", "mid64", "mid128"])
+def test_frame_major_temporal_list_keeps_the_same_elements(name):
+    """The temporal mask is one set of (query, key) pairs; the two list patterns only cover it
+    with tiles in different token orders.  Every pair the element mask keeps must lie in a
+    kept tile of BOTH lists (in their own orders), and each list must be minimal: every kept
+    tile holds at least one kept pair."""
+    g = O.Geometry.from_config(get_config(name))
+    nq, nk = O.n_tiles(g)
+    pos_of = O.layout_perm(g)                    # position of original token n in the transformed order
+    m = O.temporal_mask(g)                       # original order
+    for pattern, where in ((O.TEMPORAL_FRAME_MAJOR, np.arange(g.N)), (O.TEMPORAL, pos_of)):
+        rp, ci = O.tile_list(g, pattern)
+        kept = np.zeros((nq, nk), dtype=bool)
+        for a in range(nq):
+            kept[a, ci[rp[a]:rp[a + 1]]] = True
+        qi, kj = np.nonzero(m)
+        ta, tb = where[qi] // g.block_m, where[kj] // g.block_n
+        assert kept[ta, tb].all()
+        hit = np.zeros((nq, nk), dtype=bool)
+        hit[ta, tb] = True
+        assert np.array_equal(hit, kept)
