@@ -33,6 +33,9 @@ def parse():
     ap.add_argument("--dense-reps", type=int, default=3)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--profile-percent", type=float, default=None,
+                    help="percentage of the query rows that online profiling samples (default: the workload's "
+                         "1 %%; the paper's ablation uses 0.1, 1, 5 and 100)")
     ap.add_argument("--without-layout-transform", action="store_true",
                     help="also time the comparison arm of Sec. 5.5: temporal heads left in frame-major order "
                          "with the frame-major temporal tile list (no layout kernels)")
@@ -122,7 +125,8 @@ def main():
     BH = B * H
 
     q, k, v = make_qkv(cfg, device="cuda")
-    rows_np = sample_rows(cfg)
+    rows_np = sample_rows(cfg) if args.profile_percent is None else \
+        sample_rows(cfg, t=max(1, min(cfg["N"], int(np.ceil(cfg["N"] * args.profile_percent / 100.0)))))
     t = len(rows_np)
     rows = torch.from_numpy(rows_np).cuda()
     lists_np = [S.svg_tile_list_build(sh, p) for p in (0, 1)]
