@@ -124,8 +124,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     const int unit = loc / pairs_per_xcd;
     const int pair = xcd * pairs_per_xcd + (loc - unit * pairs_per_xcd);
     if (unit >= a.nsplit + 2 || pair >= pairs) return;
-    variant = unit < a.nsplit ? 0 : unit - a.nsplit + 1;     // 0 unmasked, 1 spatial, 2 temporal
-    chunk = unit < a.nsplit ? unit : 0;
+    // the two masked passes first: their workgroups are the longest ones (mask work on top
+    // of about as many tiles), so they should not be the last to start
+    variant = unit < 2 ? unit + 1 : 0;                       // 0 unmasked, 1 spatial, 2 temporal
+    chunk = unit < 2 ? 0 : unit - 2;
     bh = pair / a.nqt;
     grp = pair - bh * a.nqt;
   } else {
@@ -146,6 +148,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     grp = lid - bh * a.nqt;
     if (a.reverse_q) grp = a.nqt - 1 - grp;
   }
+
+  // profile: the unmasked pass needs no key codes, tile summaries or element masks (only the
+  // ragged end of the sequence, handled like in the dense pass)
+  const bool masked = MODE == kProfile && __builtin_amdgcn_readfirstlane(variant) != 0;
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -463,7 +469,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
         if (V_UNITS % THREADS == 0 || u < V_UNITS) store_v_unit(vb, u / CPR, u % CPR, vst[i]);
       }
     }
-    if (MODE == kProfile && tid < BN) {
+    if (MODE == kProfile && masked && tid < BN) {
       // per-key mask code: the key's frame (spatial) or in-frame position (temporal), or
       // "kept by every query" (text / sink key, unmasked pass), or "out of range"
       const int key = col * BN + tid;
@@ -549,8 +555,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     const int halves = LT == 1 ? 3 : (col & 3);
 
     // profile: does this wavefront need the tile at all, and does it need per-element masks?
-    bool skip = false, need_masks = MODE == kProfile;
-    if (MODE == kProfile) {
+    bool skip = false, need_masks = MODE == kProfile && masked;
+    if (MODE == kProfile && masked) {
       const int cmin = tile_info[buf * 4 + 0], cmax = tile_info[buf * 4 + 1], flags = tile_info[buf * 4 + 2];
       bool lane_all = (flags & 6) == 0, lane_none = (flags & 5) == 0;
       if (cmax >= cmin) {       // the tile has coordinate keys
@@ -607,7 +613,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
 
       __builtin_amdgcn_s_setprio(0);
       // ---- masking.  sacc[kb][4 i + jj] belongs to key  col*BN + 32 kb + 8 i + 4 g + jj.
-      if (MODE == kProfile) {
+      if (MODE == kProfile && masked) {
         if (need_masks) {
 #pragma unroll
           for (int kb = 0; kb < KB; ++kb)

@@ -24,7 +24,7 @@ int make_geo(const svg_shape_t* s, Geo* g);
 
 // Key ranges the unmasked profiling pass is cut into (so that its workgroups are about
 // as long as those of the two masked passes, which skip most key tiles).
-inline int profile_splits(const Geo& g) { return g.nk >= 32 ? 4 : 1; }
+inline int profile_splits(const Geo& g) { return g.nk >= 1024 ? 8 : g.nk >= 32 ? 4 : 1; }
 
 // Bytes of workspace svg_profile_heads uses for t rows.
 inline size_t profile_workspace_bytes(const Geo& g, int t) {
