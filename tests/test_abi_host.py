@@ -108,10 +108,28 @@ def test_tile_list_geometry_variants():
             cfg = dict(base, F=F, P=P, T=T, text_first=tf, w_s=ws, w_t=wt, block_m=bm, block_n=bn,
                        sink_first_frame=sink)
             sh, g = S.shape_from_config(cfg), O.Geometry.from_config(cfg)
-            for pattern in (0, 1):
+            for pattern in (0, 1, 2):
                 rp, ci = S.svg_tile_list_build(sh, pattern)
                 orp, oci = O.tile_list(g, pattern)
                 assert np.array_equal(rp, orp) and np.array_equal(ci, oci), (cfg, pattern)
+
+
+def test_tile_list_random_geometries():
+    """Seeded random small geometries (frames, positions, text length and side, windows, sink,
+    both tile shapes), all three list patterns, host builder against the oracle's brute force."""
+    rng = np.random.default_rng(2025)
+    base = dict(get_config("mid64"), B=1, H=1)
+    for _ in range(60):
+        F, P = int(rng.integers(1, 9)), int(rng.integers(1, 150))
+        T = int(rng.choice([0, 0, 1, 17, 64, 130]))
+        bm, bn = ((128, 64), (32, 32))[int(rng.integers(2))]
+        cfg = dict(base, F=F, P=P, T=T, text_first=int(rng.integers(2)), w_s=int(rng.integers(0, F + 1)),
+                   w_t=int(rng.integers(0, P + 1)), block_m=bm, block_n=bn, sink_first_frame=int(rng.integers(2)))
+        sh, g = S.shape_from_config(cfg), O.Geometry.from_config(cfg)
+        for pattern in (0, 1, 2):
+            rp, ci = S.svg_tile_list_build(sh, pattern)
+            orp, oci = O.tile_list(g, pattern)
+            assert np.array_equal(rp, orp) and np.array_equal(ci, oci), (cfg, pattern)
 
 
 def test_tile_list_capacity_and_size_query():

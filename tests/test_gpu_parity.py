@@ -294,6 +294,37 @@ def test_degenerate_geometries(geo, blocks):
     assert_attn_close(od[0, 0], O.dense_attention_head(f64(q)[0, 0], f64(k)[0, 0], f64(v)[0, 0], g))
 
 
+def test_random_geometries_whole_layer():
+    """Seeded random geometries (frames, positions, text length and side, windows, sink, head
+    dimension, tile shape): profiling, both layouts, block-sparse attention and the dense pass
+    against the oracle."""
+    rng = np.random.default_rng(4242)
+    for case in range(12):
+        F, P = int(rng.integers(1, 8)), int(rng.integers(1, 260))
+        T = int(rng.choice([0, 1, 17, 64, 130]))
+        bm, bn = ((128, 64), (32, 32))[int(rng.integers(2))]
+        cfg = dict(get_config("mid64"), B=1, H=2, F=F, P=P, T=T, D=int(rng.choice([64, 128])),
+                   text_first=int(rng.integers(2)), w_s=int(rng.integers(0, F + 1)), w_t=int(rng.integers(0, P + 1)),
+                   sink_first_frame=int(rng.integers(2)), block_m=bm, block_n=bn, spatial_heads=[0])
+        cfg["N"] = F * P + T
+        sh, g = S.shape_from_config(cfg), O.Geometry.from_config(cfg)
+        q, k, v = make_plain_qkv(1, 2, g.N, g.D, seed=100 + case)
+        qc, kc, vc = q.cuda(), k.cuda(), v.cuda()
+        rows = np.unique(rng.integers(0, g.N, size=min(g.N, 40))).astype(np.int32)
+        labels, mse = gpu_profile(sh, qc, kc, vc, rows)
+        omse, olab = O.profile_heads(f64(q), f64(k), f64(v), rows, g)
+        assert np.allclose(mse.cpu().numpy().reshape(omse.shape), omse, rtol=0.05, atol=2e-5), (cfg, case)
+        lab = torch.tensor([0, 1], dtype=torch.uint8, device="cuda")
+        o = gpu_layer(sh, qc, kc, vc, lab)
+        ref = O.svg_attention_layer(f64(q), f64(k), f64(v), np.array([[0, 1]]), g)
+        for h in range(2):
+            assert_attn_close(o[0, h], ref[0, h], f"case {case} {cfg} head {h}")
+        od = torch.zeros_like(qc)
+        S.svg_dense_attn_fwd(sh, qc, kc, vc, od)
+        torch.cuda.synchronize()
+        assert_attn_close(od[0, 1], O.dense_attention_head(f64(q)[0, 1], f64(k)[0, 1], f64(v)[0, 1], g))
+
+
 def test_large_logits_do_not_overflow():
     """Row maxima far from zero (|logit| ~ 60): the online softmax must stay finite."""
     cfg, sh, g = setup("mid64")
