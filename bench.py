@@ -3,9 +3,11 @@
 
 A step is one pass of the whole hot path over one synthetic layer input that is
 already resident in HBM: online profiling (three masked attentions over the
-sampled rows + MSE + label), layout transform of q, k, v, block-sparse attention
-over the kept tiles, inverse layout transform of o.  The in-library dense
-attention is timed beside it, and the CPU oracle is timed on a bounded sample.
+sampled rows + MSE + label), layout transform of k and v, block-sparse attention
+over the kept tiles with the layout transform of q and the inverse transform of o
+folded into the kernel (--four-layout-passes: as four separate passes over q, k, v
+and o).  The in-library dense attention is timed beside it, and the CPU oracle is
+timed on a bounded sample.
 
 Prints ONE JSON line on stdout.
 """
@@ -39,6 +41,9 @@ def parse():
     ap.add_argument("--without-layout-transform", action="store_true",
                     help="also time the comparison arm of Sec. 5.5: temporal heads left in frame-major order "
                          "with the frame-major temporal tile list (no layout kernels)")
+    ap.add_argument("--four-layout-passes", action="store_true",
+                    help="time the pipeline with q, k, v and o all going through the layout kernels, instead of "
+                         "the default where the attention kernel gathers q rows and scatters o rows itself")
     ap.add_argument("--only", default="", help="time a single stage only (profile|layout|sparse|dense); "
                     "used for per-kernel rocprofv3 runs")
     return ap.parse_args()
@@ -143,19 +148,26 @@ def main():
     def stage_profile():
         S.svg_profile_heads(sh, q, k, v, rows, t, labels, mse, ws, ws_bytes)
 
+    folded = not args.four_layout_passes
+
     def stage_layout_fwd():
-        S.svg_layout_fwd(sh, q, qp, labels)
+        if not folded:
+            S.svg_layout_fwd(sh, q, qp, labels)
         S.svg_layout_fwd(sh, k, kp, labels)
         S.svg_layout_fwd(sh, v, vp, labels)
 
     def stage_sparse():
-        S.svg_sparse_attn_fwd(sh, qp, kp, vp, op, labels, *lists)
+        if folded:
+            S.svg_sparse_attn_fwd_ex(sh, q, kp, vp, o, labels, *lists, flags=S.SVG_ATTN_QO_TOKEN_ORDER)
+        else:
+            S.svg_sparse_attn_fwd(sh, qp, kp, vp, op, labels, *lists)
 
     def stage_layout_inv():
         S.svg_layout_inv(sh, op, o, labels)
 
-    stages = [("profile", stage_profile), ("layout_fwd", stage_layout_fwd),
-              ("sparse_attn", stage_sparse), ("layout_inv", stage_layout_inv)]
+    stages = [("profile", stage_profile), ("layout_fwd", stage_layout_fwd), ("sparse_attn", stage_sparse)]
+    if not folded:
+        stages.append(("layout_inv", stage_layout_inv))
 
     def step(marks=None):
         for name, fn in stages:
@@ -172,7 +184,8 @@ def main():
         # single-stage mode for per-kernel profiling
         step()
         torch.cuda.synchronize()
-        fn = {"profile": stage_profile, "layout": lambda: (stage_layout_fwd(), stage_layout_inv()),
+        fn = {"profile": stage_profile,
+              "layout": lambda: (stage_layout_fwd(), None if folded else stage_layout_inv()),
               "sparse": stage_sparse,
               "dense": lambda: S.svg_dense_attn_fwd(sh, q, k, v, o)}[args.only]
         for _ in range(args.warmup):
@@ -235,8 +248,8 @@ def main():
     layout_bytes = 2.0 * n_temporal * N * D * 2 + 2.0 * (BH - n_temporal) * N * D * 2   # read + write, all heads
     out = {
         "metric": "effective TFLOP/s of one sparse attention layer at %dk tokens "
-                  "(4*N^2*D*H / ms per layer; profile + layout + block-sparse attention + inverse layout)"
-                  % round(N / 1000),
+                  "(4*N^2*D*H / ms per layer; profile + layout + block-sparse attention + inverse layout%s)"
+                  % (round(N / 1000), ", the layout of q and o folded into the attention kernel" if folded else ""),
         "value": dense_flops / (wall_ms * 1e-3) / 1e12,
         "unit": "TFLOP/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
@@ -250,8 +263,9 @@ def main():
         "dense_ms": dense_ms,
         "dense_tflops": None if dense_ms is None else dense_flops / (dense_ms * 1e-3) / 1e12,
         "speedup_vs_dense": None if dense_ms is None else dense_ms / wall_ms,
-        "layout_gbs": {"fwd_qkv": 3 * layout_bytes / (breakdown["layout_fwd"] * 1e-3) / 1e9,
-                       "inv_o": layout_bytes / (breakdown["layout_inv"] * 1e-3) / 1e9},
+        "layout_passes": "k v (q and o inside the attention kernel)" if folded else "q k v o",
+        "layout_gbs": {"fwd": (2 if folded else 3) * layout_bytes / (breakdown["layout_fwd"] * 1e-3) / 1e9,
+                       "inv_o": None if folded else layout_bytes / (breakdown["layout_inv"] * 1e-3) / 1e9},
         # the three masked passes of Alg. 1 counted in full (3 x 4 t N D per head), although the
         # kernel skips the key tiles no sampled row of a workgroup keeps
         "profile_nominal_tflops": 3 * 4.0 * t * N * D * BH / (breakdown["profile"] * 1e-3) / 1e12,

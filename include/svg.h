@@ -156,6 +156,23 @@ int svg_sparse_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, 
                         void* stream);
 
 /*
+ * svg_sparse_attn_fwd with options.  flags == 0 is svg_sparse_attn_fwd itself.
+ * SVG_ATTN_QO_TOKEN_ORDER folds two of the four layout passes of Sec. 4.2 into the
+ * attention kernel (the paper fuses the transformation into its kernels as well,
+ * Sec. 4.3): q is read and o is written in the original token order for every head,
+ * the kernel gathering the query rows of a temporal head's tile and scattering its
+ * output rows through the permutation; only k and v of temporal heads must be in
+ * P-outer order.  Results are bit-identical to svg_layout_fwd(q) ->
+ * svg_sparse_attn_fwd -> svg_layout_inv(o).  Unknown flag bits: SVG_ERR_INVALID_ARG.
+ */
+enum { SVG_ATTN_QO_TOKEN_ORDER = 1 };
+int svg_sparse_attn_fwd_ex(const svg_shape_t* shape, const void* q, const void* k, const void* v,
+                           void* o, const uint8_t* labels, const int32_t* row_ptr_s,
+                           const int32_t* col_idx_s, const int32_t* row_ptr_t,
+                           const int32_t* col_idx_t, uint32_t flags, void* workspace,
+                           size_t workspace_bytes, void* stream);
+
+/*
  * Dense attention forward, o = softmax(scale * q k^T) v per head: the baseline
  * the paper measures against (Sec. 5.3) and the pass used on the dense warm-up
  * steps (Sec. 5.1).  Same tensors and precision as svg_sparse_attn_fwd; every

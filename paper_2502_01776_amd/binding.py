@@ -18,11 +18,12 @@ LIB_PATH = os.path.join(_HERE, "libsvg_gfx950.so")
 SVG_HEAD_SPATIAL = 0
 SVG_HEAD_TEMPORAL = 1
 SVG_LIST_TEMPORAL_FRAME_MAJOR = 2   # list pattern only: temporal mask without the layout transformation
+SVG_ATTN_QO_TOKEN_ORDER = 1          # svg_sparse_attn_fwd_ex: q read and o written in token order
 SVG_OK = 0
 
 EXPORTS = ("svg_strerror", "svg_version", "svg_last_hip_error", "svg_workspace_bytes", "svg_tile_counts",
            "svg_tile_list_build", "svg_profile_heads", "svg_layout_fwd", "svg_layout_inv",
-           "svg_sparse_attn_fwd", "svg_dense_attn_fwd")
+           "svg_sparse_attn_fwd", "svg_sparse_attn_fwd_ex", "svg_dense_attn_fwd")
 
 
 class SvgShape(C.Structure):
@@ -77,6 +78,8 @@ def lib():
             f.argtypes = [sp, vp, vp, vp, vp]
         L.svg_sparse_attn_fwd.restype = C.c_int
         L.svg_sparse_attn_fwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.svg_sparse_attn_fwd_ex.restype = C.c_int
+        L.svg_sparse_attn_fwd_ex.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_uint32, vp, C.c_size_t, vp]
         L.svg_dense_attn_fwd.restype = C.c_int
         L.svg_dense_attn_fwd.argtypes = [sp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         _lib = L
@@ -169,6 +172,14 @@ def svg_sparse_attn_fwd(shape, q, k, v, o, labels, row_ptr_s, col_idx_s, row_ptr
                                      _ptr(row_ptr_s), _ptr(col_idx_s), _ptr(row_ptr_t),
                                      _ptr(col_idx_t), _ptr(workspace), int(workspace_bytes),
                                      _stream(stream)), "svg_sparse_attn_fwd")
+
+
+def svg_sparse_attn_fwd_ex(shape, q, k, v, o, labels, row_ptr_s, col_idx_s, row_ptr_t, col_idx_t,
+                           flags=0, workspace=None, workspace_bytes=0, stream=None):
+    _check(lib().svg_sparse_attn_fwd_ex(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(o), _ptr(labels),
+                                        _ptr(row_ptr_s), _ptr(col_idx_s), _ptr(row_ptr_t),
+                                        _ptr(col_idx_t), int(flags), _ptr(workspace),
+                                        int(workspace_bytes), _stream(stream)), "svg_sparse_attn_fwd_ex")
 
 
 def svg_dense_attn_fwd(shape, q, k, v, o, workspace=None, workspace_bytes=0, stream=None):

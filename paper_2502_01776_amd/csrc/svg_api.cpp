@@ -58,13 +58,14 @@ int svg_profile_heads(const svg_shape_t* shape, const void* q, const void* k, co
                              static_cast<hipStream_t>(stream));
 }
 
-int svg_sparse_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, const void* v,
-                        void* o, const uint8_t* labels, const int32_t* row_ptr_s,
-                        const int32_t* col_idx_s, const int32_t* row_ptr_t,
-                        const int32_t* col_idx_t, void* workspace, size_t workspace_bytes,
-                        void* stream) {
+int svg_sparse_attn_fwd_ex(const svg_shape_t* shape, const void* q, const void* k, const void* v,
+                           void* o, const uint8_t* labels, const int32_t* row_ptr_s,
+                           const int32_t* col_idx_s, const int32_t* row_ptr_t,
+                           const int32_t* col_idx_t, uint32_t flags, void* workspace,
+                           size_t workspace_bytes, void* stream) {
   (void)workspace;
   (void)workspace_bytes;
+  if (flags & ~(uint32_t)SVG_ATTN_QO_TOKEN_ORDER) return SVG_ERR_INVALID_ARG;
   Geo g;
   int rc = svg::make_geo(shape, &g);
   if (rc != SVG_OK) return rc;
@@ -75,7 +76,17 @@ int svg_sparse_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, 
   const size_t bytes = tensor_bytes(g);
   if (overlap(o, q, bytes) || overlap(o, k, bytes) || overlap(o, v, bytes)) return SVG_ERR_ALIAS;
   return svg::launch_attention(g, q, k, v, o, labels, row_ptr_s, col_idx_s, row_ptr_t, col_idx_t,
-                               true, static_cast<hipStream_t>(stream));
+                               true, (flags & SVG_ATTN_QO_TOKEN_ORDER) != 0,
+                               static_cast<hipStream_t>(stream));
+}
+
+int svg_sparse_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, const void* v,
+                        void* o, const uint8_t* labels, const int32_t* row_ptr_s,
+                        const int32_t* col_idx_s, const int32_t* row_ptr_t,
+                        const int32_t* col_idx_t, void* workspace, size_t workspace_bytes,
+                        void* stream) {
+  return svg_sparse_attn_fwd_ex(shape, q, k, v, o, labels, row_ptr_s, col_idx_s, row_ptr_t,
+                                col_idx_t, 0u, workspace, workspace_bytes, stream);
 }
 
 int svg_dense_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, const void* v,
@@ -90,7 +101,7 @@ int svg_dense_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, c
   const size_t bytes = tensor_bytes(g);
   if (overlap(o, q, bytes) || overlap(o, k, bytes) || overlap(o, v, bytes)) return SVG_ERR_ALIAS;
   return svg::launch_attention(g, q, k, v, o, nullptr, nullptr, nullptr, nullptr, nullptr, false,
-                               static_cast<hipStream_t>(stream));
+                               false, static_cast<hipStream_t>(stream));
 }
 
 }  // extern "C"

@@ -205,9 +205,20 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     __syncthreads();
   }
 
+  // sparse: this head's pattern; with q and o kept in token order, the row of a temporal
+  // head that this lane reads and writes is the token whose transformed position is qrow
+  // (Sec. 4.2: position off + p F + f holds token off + f P + p)
+  const int pat = MODE == kSparse && a.labels ? (a.labels[bh] != 0) : 0;
+  int io_row = qrow;
+  if (MODE == kSparse && a.qo_token_order && pat && qrow >= a.off && qrow < a.video_end) {
+    const int vq = qrow - a.off;
+    const int p = vq / a.F;
+    io_row = a.off + (vq - p * a.F) * a.P + p;
+  }
+
   bf16x8 qreg[DS];     // lane (g, r) holds Q[qrow][16 s + 8 g .. +8]
   {
-    const __bf16* qp = a.q + (head + qrow) * D + g * 8;
+    const __bf16* qp = a.q + (head + io_row) * D + g * 8;
 #pragma unroll
     for (int s = 0; s < DS; ++s) qreg[s] = *reinterpret_cast<const bf16x8*>(qp + s * 16);
   }
@@ -226,7 +237,6 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   int lj = 0, lend = 0;              // sparse: cursor and end in col_idx;  dense: counter and nk
   int lbeg = 0, lleft = 0;           // sparse: start of the list row, entries still to hand out
   if (MODE == kSparse) {
-    const int pat = a.labels ? (a.labels[bh] != 0) : 0;
     const int32_t* rp = a.row_ptr[pat];
     cols = a.col_idx[pat];
     lbeg = __builtin_amdgcn_readfirstlane(rp[grp]);
@@ -742,7 +752,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     }
   } else {
     if (qslot < a.N) {
-      __bf16* op = static_cast<__bf16*>(a.o) + (head + qslot) * D;
+      __bf16* op = static_cast<__bf16*>(a.o) + (head + io_row) * D;
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -913,9 +923,10 @@ AttnArgs base_args(const Geo& g, const void* q, const void* k, const void* v, vo
 int launch_attention(const Geo& g, const void* q, const void* k, const void* v, void* o,
                      const uint8_t* labels, const int32_t* row_ptr_s, const int32_t* col_idx_s,
                      const int32_t* row_ptr_t, const int32_t* col_idx_t, bool sparse,
-                     hipStream_t stream) {
+                     bool qo_token_order, hipStream_t stream) {
   AttnArgs a = base_args(g, q, k, v, o);
   a.labels = labels;
+  a.qo_token_order = sparse && qo_token_order ? 1 : 0;
   a.row_ptr[0] = row_ptr_s; a.col_idx[0] = col_idx_s;
   a.row_ptr[1] = row_ptr_t; a.col_idx[1] = col_idx_t;
   // query tiles holding text rows keep every key tile: start them first

@@ -37,6 +37,7 @@ struct AttnArgs {
   int nqt;                    // workgroups per head: query tiles (dense, sparse) or ceil(t / rows per workgroup) (profile)
   int reverse_q;              // process query tiles last-to-first (heavy text-suffix tiles first)
   int total;                  // logical workgroups
+  int qo_token_order;         // sparse: q is read and o written in token order also for temporal heads
   float scale_log2;           // softmax scale * log2(e)
   int off, video_end, F, P, w_s, w_t, sink;
 };

@@ -54,6 +54,17 @@ def gpu_layer(shape, q, k, v, labels, lists=None):
     return o
 
 
+def gpu_layer_token_order(shape, q, k, v, labels, lists=None):
+    """layout fwd (k,v only) -> block-sparse attention reading q and writing o in token order."""
+    lists = lists or device_tile_lists(shape)
+    kp, vp, o = (torch.empty_like(q) for _ in range(3))
+    S.svg_layout_fwd(shape, k, kp, labels)
+    S.svg_layout_fwd(shape, v, vp, labels)
+    S.svg_sparse_attn_fwd_ex(shape, q, kp, vp, o, labels, *lists, flags=S.SVG_ATTN_QO_TOKEN_ORDER)
+    torch.cuda.synchronize()
+    return o
+
+
 def assert_attn_close(got: torch.Tensor, ref: np.ndarray, what=""):
     g = f64(got)
     assert np.isfinite(g).all(), f"{what}: non-finite output"

@@ -40,6 +40,14 @@ def test_full_size_layer_sampled(name):
     assert np.array_equal(lab, planted_labels(cfg)), "profiled labels differ from the planted ones"
     nq, nk = O.n_tiles(g)
 
+    # the pipeline bench.py times (q read and o written in token order by the attention kernel
+    # itself) gives the same bits as the four-pass pipeline checked below
+    o2 = torch.empty_like(o)
+    S.svg_sparse_attn_fwd_ex(sh, q, kp, vp, o2, labels, *device_tile_lists(sh), flags=S.SVG_ATTN_QO_TOKEN_ORDER)
+    torch.cuda.synchronize()
+    assert torch.equal(o2.view(torch.int16), o.view(torch.int16))
+    del o2
+
     # profiling: two heads (one of each label) recomputed by the oracle on a subset of rows
     sub = rows[:: max(1, len(rows) // 96)]
     for h in (int(np.nonzero(lab == O.SPATIAL)[0][0]), int(np.nonzero(lab == O.TEMPORAL)[0][0])):

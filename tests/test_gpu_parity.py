@@ -7,7 +7,8 @@ import torch
 import paper_2502_01776_amd as S
 from oracle import svg_oracle as O
 from workloads import get_config, make_qkv, make_plain_qkv, sample_rows, planted_labels
-from helpers import (f64, bits, dev_i32, device_tile_lists, gpu_profile, gpu_layer, assert_attn_close,
+from helpers import (f64, bits, dev_i32, device_tile_lists, gpu_profile, gpu_layer, gpu_layer_token_order,
+                     assert_attn_close,
                      labels_match)
 
 pytestmark = pytest.mark.gpu
@@ -242,6 +243,44 @@ def test_whole_layer(name):
     for b in range(g.B):
         for h in range(g.H):
             assert_attn_close(o[b, h], ref[b, h], f"{name} layer b{b} h{h}")
+
+
+@pytest.mark.parametrize("name", SMALL)
+@pytest.mark.parametrize("sink", [0, 1])
+def test_layer_with_q_and_o_in_token_order(name, sink):
+    """The attention kernel gathering q rows and scattering o rows itself (two of the four layout
+    passes folded in): against the oracle, and bit-identical to the four-pass pipeline."""
+    cfg, sh, g = setup(name, sink_first_frame=sink)
+    q, k, v = make_qkv(cfg)
+    qc, kc, vc = q.cuda(), k.cuda(), v.cuda()
+    lab_np = planted_labels(cfg)
+    labels = torch.from_numpy(lab_np).cuda()
+    o = gpu_layer_token_order(sh, qc, kc, vc, labels)
+    ref = O.svg_attention_layer(f64(q), f64(k), f64(v), lab_np.reshape(g.B, g.H), g)
+    for b in range(g.B):
+        for h in range(g.H):
+            assert_attn_close(o[b, h], ref[b, h], f"{name} token-order layer b{b} h{h}")
+    o4 = gpu_layer(sh, qc, kc, vc, labels)
+    assert torch.equal(o.view(torch.int16), o4.view(torch.int16))
+    # every head temporal, no label array semantics: labels == all ones
+    ones = torch.ones_like(labels)
+    assert torch.equal(gpu_layer_token_order(sh, qc, kc, vc, ones).view(torch.int16),
+                       gpu_layer(sh, qc, kc, vc, ones).view(torch.int16))
+
+
+def test_extended_entry_point_rejects_unknown_flags():
+    cfg, sh, g = setup("mid64")
+    q, k, v = (x.cuda() for x in make_qkv(cfg))
+    o = torch.empty_like(q)
+    lists = device_tile_lists(sh)
+    with pytest.raises(S.SvgError):
+        S.svg_sparse_attn_fwd_ex(sh, q, k, v, o, None, *lists, flags=2)
+    # flags == 0 is the plain entry point
+    o0 = torch.empty_like(q)
+    S.svg_sparse_attn_fwd_ex(sh, q, k, v, o, None, *lists, flags=0)
+    S.svg_sparse_attn_fwd(sh, q, k, v, o0, None, *lists)
+    torch.cuda.synchronize()
+    assert torch.equal(o.view(torch.int16), o0.view(torch.int16))
 
 
 def test_results_are_deterministic():
