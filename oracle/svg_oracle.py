@@ -280,3 +280,78 @@ def svg_attention_layer(q, k, v, labels, g: Geometry):
                                           layout_fwd(v[b, h], g), rp, ci, g)
                 out[b, h] = layout_inv(o, g)
     return out
+
+
+# ----------------------------------------------------------------------------
+# FP8 attention (Sec. 4.3 "Quantization", Sec. 5.2): the block-sparse pass on q, k, v
+# quantised to 8-bit floating point.
+#
+# Reading (the paper only says that FP8 quantisation is applied to the sparse attention and
+# names no format or scaling): the OCP 8-bit format E4M3 (1 sign, 4 exponent bits with bias 7,
+# 3 mantissa bits, subnormals, largest finite value 448, no infinities) with one scale per
+# head and tensor, scale = max|x| / 448, round to nearest even.  The decisions that produce
+# the integer codes (the scale, the division by it, the rounding) are taken in float32, the
+# precision the kernel takes them in; everything after the codes is float64.  The oracle
+# defines the result as exact attention over the DEQUANTISED tensors; that the kernel also
+# rounds the attention weights to E4M3 before the second product is covered by the tolerance.
+# ----------------------------------------------------------------------------
+E4M3_MAX = 448.0
+
+
+def e4m3_decode(codes) -> np.ndarray:
+    """Value of each E4M3 code (uint8) by the format's definition; 0x7f / 0xff are NaN."""
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    sign = np.where(c & 0x80, -1.0, 1.0)
+    e = (c >> 3) & 15
+    m = (c & 7).astype(np.float64)
+    val = np.where(e == 0, m * 2.0 ** -9, (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64)))
+    val = np.where((e == 15) & ((c & 7) == 7), np.nan, val)
+    return sign * val
+
+
+def e4m3_encode(y) -> np.ndarray:
+    """Nearest E4M3 code of each value, ties to the even mantissa, magnitudes above 448
+    clamped to 448 (the kernel clamps before converting)."""
+    y = np.asarray(y, dtype=np.float64)
+    a = np.minimum(np.abs(y), E4M3_MAX)
+    code = np.zeros(a.shape, dtype=np.int64)
+    sub = a < 2.0 ** -6
+    code[sub] = np.rint(a[sub] * 512.0).astype(np.int64)          # multiples of 2^-9; 8 is the first normal
+    an = a[~sub]
+    _, ex = np.frexp(an)                                           # an = mant * 2^ex, mant in [0.5, 1)
+    e = ex.astype(np.int64) - 1
+    m = np.rint(an / np.exp2((e - 3).astype(np.float64))).astype(np.int64)   # 8 .. 16
+    carry = m == 16
+    e = e + carry
+    m = np.where(carry, 8, m)
+    code[~sub] = ((e + 7) << 3) | (m - 8)
+    code |= np.where(np.signbit(y), 0x80, 0)
+    return code.astype(np.uint8)
+
+
+def fp8_quantize_head(x):
+    """x [N,D] (values exactly representable in float32) -> (codes uint8 [N,D], scale float32)
+    with x ~ decode(codes) * scale, scale = max|x| / 448 (1 if x is all zero)."""
+    x32 = np.asarray(x, dtype=np.float32)
+    amax = np.float32(np.max(np.abs(x32))) if x32.size else np.float32(0)
+    scale = np.float32(amax / np.float32(E4M3_MAX)) if amax > 0 else np.float32(1)
+    return e4m3_encode(x32 / scale), scale
+
+
+def fp8_dequantize(codes, scale) -> np.ndarray:
+    return e4m3_decode(codes) * np.float64(scale)
+
+
+def svg_attention_layer_fp8(q, k, v, labels, g: Geometry):
+    """The sparse pass of one layer with q, k, v of every head quantised to E4M3 first
+    (per head and tensor); otherwise svg_attention_layer.  The quantisation is elementwise
+    with one scale per head, so it commutes with the layout transformation."""
+    dq = np.empty_like(q)
+    dk = np.empty_like(k)
+    dv = np.empty_like(v)
+    for b in range(g.B):
+        for h in range(g.H):
+            for src, dst in ((q, dq), (k, dk), (v, dv)):
+                codes, scale = fp8_quantize_head(src[b, h])
+                dst[b, h] = fp8_dequantize(codes, scale)
+    return svg_attention_layer(dq, dk, dv, labels, g)

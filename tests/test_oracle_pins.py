@@ -487,3 +487,81 @@ def test_frame_major_temporal_list_keeps_the_same_elements(name):
         hit = np.zeros((nq, nk), dtype=bool)
         hit[ta, tb] = True
         assert np.array_equal(hit, kept)
+
+
+# ----------------------------------------------------------------------------- FP8 (E4M3)
+def test_e4m3_decode_follows_the_format_definition():
+    """Values fixed by the OCP 8-bit floating point format: bias 7, three mantissa bits,
+    subnormals in steps of 2^-9, largest finite value 448, S.1111.111 is NaN."""
+    want = {0x00: 0.0, 0x01: 2.0 ** -9, 0x07: 7 * 2.0 ** -9, 0x08: 2.0 ** -6, 0x30: 0.5, 0x38: 1.0,
+            0x3c: 1.5, 0x40: 2.0, 0x45: 3.25, 0x77: 240.0, 0x7e: 448.0, 0xb8: -1.0, 0xfe: -448.0}
+    for code, val in want.items():
+        assert O.e4m3_decode(np.array([code], np.uint8))[0] == val, hex(code)
+    assert np.isnan(O.e4m3_decode(np.array([0x7f, 0xff], np.uint8))).all()
+    pos = O.e4m3_decode(np.arange(0, 0x7f, dtype=np.uint8))
+    assert (np.diff(pos) > 0).all()                                   # codes ascend with the value
+    assert np.array_equal(O.e4m3_decode(np.arange(0x80, 0xff, dtype=np.uint8)), -pos)
+
+
+def test_e4m3_encode_is_nearest_with_ties_to_even():
+    codes = np.array([c for c in range(256) if (c & 0x7f) != 0x7f and c != 0x80], np.uint8)
+    vals = O.e4m3_decode(codes)
+    assert np.array_equal(O.e4m3_encode(vals), codes)                 # every finite code is a fixed point
+    # brute force: the encoded value is a nearest representable one
+    rng = np.random.default_rng(5)
+    y = np.concatenate([rng.normal(0, 1, 4000) * np.exp2(rng.integers(-12, 9, 4000)), [0.0, 447.9, 448.0, 500.0, -1e9]])
+    got = O.e4m3_decode(O.e4m3_encode(y))
+    table = np.sort(O.e4m3_decode(codes))
+    yc = np.clip(y, -448.0, 448.0)
+    best = np.abs(table[None, :] - yc[:, None]).min(axis=1)
+    assert np.array_equal(np.abs(got - yc), best)
+    assert np.array_equal(np.sign(got) * (got != 0), np.sign(yc) * (got != 0))
+    # midpoints between neighbours go to the code with the even mantissa
+    pos = O.e4m3_decode(np.arange(0, 0x7f, dtype=np.uint8))
+    mid = (pos[:-1] + pos[1:]) / 2
+    enc = O.e4m3_encode(mid)
+    assert (enc % 2 == 0).all() and (np.abs(O.e4m3_decode(enc) - mid) == np.diff(pos) / 2).all()
+    # hand-worked: 1.0625 -> 1.0 (0x38), 1.1875 -> 1.25 (0x3a), 2^-10 -> 0, 3 * 2^-10 -> 2^-8 (0x02)
+    assert O.e4m3_encode(np.array([1.0625, 1.1875, 2.0 ** -10, 3 * 2.0 ** -10])).tolist() == [0x38, 0x3a, 0x00, 0x02]
+
+
+def test_fp8_quantize_head_scale_and_error_bound():
+    rng = np.random.default_rng(9)
+    x = torch.from_numpy(rng.normal(0, 1.3, (300, 64))).to(torch.bfloat16).to(torch.float64).numpy()
+    codes, scale = O.fp8_quantize_head(x)
+    amax = np.abs(x).max()
+    assert scale.dtype == np.float32 and scale == np.float32(np.float32(amax) / np.float32(448.0))
+    i = np.unravel_index(np.abs(x).argmax(), x.shape)
+    assert codes[i] & 0x7f == 0x7e                                    # the largest magnitude maps to 448
+    back = O.fp8_dequantize(codes, scale)
+    # nearest rounding: the error is at most half a step, a step being 2^-3 of the value's binade
+    # (2^-9 of the scale below 2^-6), plus the float32 rounding of the division
+    a = np.abs(x) / float(scale)
+    step = np.where(a < 2.0 ** -6, 2.0 ** -9, np.exp2(np.floor(np.log2(np.maximum(a, 1e-30))) - 3))
+    assert (np.abs(back - x) <= float(scale) * (step / 2 + 448 * 2.0 ** -22)).all()
+    # all zero: scale 1, codes 0
+    z, s = O.fp8_quantize_head(np.zeros((4, 8)))
+    assert s == 1 and not z.any()
+
+
+def test_fp8_layer_is_the_plain_layer_when_quantisation_is_lossless():
+    """Inputs that are E4M3 values times a power of two with the largest magnitude 448 are
+    reproduced exactly, so the FP8 layer must equal the plain one bit for bit (this pins the
+    wiring: a dropped scale, a tensor quantised with another one's scale, a missing
+    dequantisation would all show)."""
+    cfg = get_config("tiny")
+    g = O.Geometry.from_config(cfg)
+    rng = np.random.default_rng(21)
+    codes = np.array([c for c in range(256) if (c & 0x7f) <= 0x5f], np.uint8)     # |value| <= 30
+    def lossless(power):
+        x = O.e4m3_decode(rng.choice(codes, size=(g.B, g.H, g.N, g.D))) * 2.0 ** power
+        x[:, :, 0, 0] = 448.0 * 2.0 ** power
+        return x
+    q, k, v = lossless(-7), lossless(-6), lossless(-4)
+    labels = np.arange(g.B * g.H).reshape(g.B, g.H) % 2
+    assert np.array_equal(O.svg_attention_layer_fp8(q, k, v, labels, g), O.svg_attention_layer(q, k, v, labels, g))
+    # and for ordinary inputs it differs from the plain layer by a few per cent, not more
+    q, k, v = (x.to(torch.float64).numpy() for x in make_qkv(cfg))
+    a, b = O.svg_attention_layer_fp8(q, k, v, labels, g), O.svg_attention_layer(q, k, v, labels, g)
+    rel = np.linalg.norm(a - b) / np.linalg.norm(b)
+    assert 1e-4 < rel < 0.1
