@@ -181,6 +181,44 @@ int svg_sparse_attn_fwd_ex(const svg_shape_t* shape, const void* q, const void* 
 int svg_dense_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, const void* v,
                        void* o, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * FP8 attention (Sec. 4.3 "Quantization", Sec. 5.2: FP8 quantisation of the sparse
+ * attention, applied at head dimension 128).  The paper names no format or scaling;
+ * this library uses OCP E4M3 (largest finite value 448) with one scale per head and
+ * tensor, scale = max|x| / 448 (1 for an all-zero head), x ~ code * scale, codes rounded
+ * to nearest even in float32.  Head dimension 128 and 128 x 64 tiles only, otherwise
+ * SVG_ERR_UNSUPPORTED.
+ *
+ * svg_fp8_quantize converts q, k, v (device bf16 [B,H,N,128], token order) into
+ *   q8      uint8 [B,H,N,128], token order
+ *   k8      uint8 [B,H,nk*64,128]: rows beyond N are zero; heads labelled temporal are
+ *           written in P-outer order (the layout transformation of Sec. 4.2 is applied on
+ *           the way, so no svg_layout_fwd is needed)
+ *   v8t     uint8 [B,H,nk,8192]: per 64-key tile a transposed image in the order the
+ *           attention kernel stages it (opaque to the caller), same head order as k8
+ *   scales  float [6*B*H]: [0,B*H) scale of q per head, then k, then v; the rest is
+ *           scratch of the call
+ * labels == NULL leaves every head in token order.  Buffer sizes in bytes:
+ * svg_fp8_buffer_bytes(shape, SVG_FP8_Q / _K / _VT / _SCALES) (0 for an unsupported shape).
+ * All buffers caller-owned, 16-byte aligned, distinct.
+ *
+ * svg_sparse_attn_fp8_fwd is svg_sparse_attn_fwd_ex(SVG_ATTN_QO_TOKEN_ORDER) on those
+ * buffers: o (device bf16 [B,H,N,128]) is written in token order for every head, labels
+ * and tile lists as for svg_sparse_attn_fwd (pass the labels given to svg_fp8_quantize).
+ * Both matrix products run on the FP8 matrix cores with fp32 accumulation; the attention
+ * weights are rounded to E4M3 for the second product and the row sums are taken over the
+ * rounded weights.
+ */
+enum { SVG_FP8_Q = 0, SVG_FP8_K = 1, SVG_FP8_VT = 2, SVG_FP8_SCALES = 3 };
+size_t svg_fp8_buffer_bytes(const svg_shape_t* shape, int which);
+int svg_fp8_quantize(const svg_shape_t* shape, const void* q, const void* k, const void* v,
+                     const uint8_t* labels, void* q8, void* k8, void* v8t, float* scales,
+                     void* stream);
+int svg_sparse_attn_fp8_fwd(const svg_shape_t* shape, const void* q8, const void* k8,
+                            const void* v8t, const float* scales, void* o, const uint8_t* labels,
+                            const int32_t* row_ptr_s, const int32_t* col_idx_s,
+                            const int32_t* row_ptr_t, const int32_t* col_idx_t, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -18,12 +18,14 @@ LIB_PATH = os.path.join(_HERE, "libsvg_gfx950.so")
 SVG_HEAD_SPATIAL = 0
 SVG_HEAD_TEMPORAL = 1
 SVG_LIST_TEMPORAL_FRAME_MAJOR = 2   # list pattern only: temporal mask without the layout transformation
+SVG_FP8_Q, SVG_FP8_K, SVG_FP8_VT, SVG_FP8_SCALES = 0, 1, 2, 3   # svg_fp8_buffer_bytes
 SVG_ATTN_QO_TOKEN_ORDER = 1          # svg_sparse_attn_fwd_ex: q read and o written in token order
 SVG_OK = 0
 
 EXPORTS = ("svg_strerror", "svg_version", "svg_last_hip_error", "svg_workspace_bytes", "svg_tile_counts",
            "svg_tile_list_build", "svg_profile_heads", "svg_layout_fwd", "svg_layout_inv",
-           "svg_sparse_attn_fwd", "svg_sparse_attn_fwd_ex", "svg_dense_attn_fwd")
+           "svg_sparse_attn_fwd", "svg_sparse_attn_fwd_ex", "svg_dense_attn_fwd",
+           "svg_fp8_buffer_bytes", "svg_fp8_quantize", "svg_sparse_attn_fp8_fwd")
 
 
 class SvgShape(C.Structure):
@@ -80,6 +82,12 @@ def lib():
         L.svg_sparse_attn_fwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.svg_sparse_attn_fwd_ex.restype = C.c_int
         L.svg_sparse_attn_fwd_ex.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_uint32, vp, C.c_size_t, vp]
+        L.svg_fp8_buffer_bytes.restype = C.c_size_t
+        L.svg_fp8_buffer_bytes.argtypes = [sp, C.c_int]
+        L.svg_fp8_quantize.restype = C.c_int
+        L.svg_fp8_quantize.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.svg_sparse_attn_fp8_fwd.restype = C.c_int
+        L.svg_sparse_attn_fp8_fwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.svg_dense_attn_fwd.restype = C.c_int
         L.svg_dense_attn_fwd.argtypes = [sp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         _lib = L
@@ -186,3 +194,20 @@ def svg_dense_attn_fwd(shape, q, k, v, o, workspace=None, workspace_bytes=0, str
     _check(lib().svg_dense_attn_fwd(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(o),
                                     _ptr(workspace), int(workspace_bytes), _stream(stream)),
            "svg_dense_attn_fwd")
+
+
+def svg_fp8_buffer_bytes(shape, which) -> int:
+    return int(lib().svg_fp8_buffer_bytes(C.byref(shape), int(which)))
+
+
+def svg_fp8_quantize(shape, q, k, v, labels, q8, k8, v8t, scales, stream=None):
+    _check(lib().svg_fp8_quantize(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(labels), _ptr(q8),
+                                  _ptr(k8), _ptr(v8t), _ptr(scales), _stream(stream)), "svg_fp8_quantize")
+
+
+def svg_sparse_attn_fp8_fwd(shape, q8, k8, v8t, scales, o, labels, row_ptr_s, col_idx_s, row_ptr_t,
+                            col_idx_t, stream=None):
+    _check(lib().svg_sparse_attn_fp8_fwd(C.byref(shape), _ptr(q8), _ptr(k8), _ptr(v8t), _ptr(scales),
+                                         _ptr(o), _ptr(labels), _ptr(row_ptr_s), _ptr(col_idx_s),
+                                         _ptr(row_ptr_t), _ptr(col_idx_t), _stream(stream)),
+           "svg_sparse_attn_fp8_fwd")

@@ -104,4 +104,49 @@ int svg_dense_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, c
                                false, static_cast<hipStream_t>(stream));
 }
 
+size_t svg_fp8_buffer_bytes(const svg_shape_t* shape, int which) {
+  Geo g;
+  if (svg::make_geo(shape, &g) != SVG_OK || g.D != 128 || g.bm != 128) return 0;
+  const size_t bh = (size_t)g.B * g.H;
+  switch (which) {
+    case SVG_FP8_Q: return bh * g.N * g.D;
+    case SVG_FP8_K:
+    case SVG_FP8_VT: return bh * g.nk * g.bn * g.D;
+    case SVG_FP8_SCALES: return 6 * bh * sizeof(float);
+    default: return 0;
+  }
+}
+
+int svg_fp8_quantize(const svg_shape_t* shape, const void* q, const void* k, const void* v,
+                     const uint8_t* labels, void* q8, void* k8, void* v8t, float* scales,
+                     void* stream) {
+  Geo g;
+  int rc = svg::make_geo(shape, &g);
+  if (rc != SVG_OK) return rc;
+  if (g.D != 128 || g.bm != 128) return SVG_ERR_UNSUPPORTED;
+  if (!q || !k || !v || !q8 || !k8 || !v8t || !scales) return SVG_ERR_INVALID_ARG;
+  if (svg::misaligned16(q) || svg::misaligned16(k) || svg::misaligned16(v) || svg::misaligned16(q8) ||
+      svg::misaligned16(k8) || svg::misaligned16(v8t) || svg::misaligned16(scales))
+    return SVG_ERR_INVALID_ARG;
+  return svg::launch_fp8_quantize(g, q, k, v, labels, q8, k8, v8t, scales,
+                                  static_cast<hipStream_t>(stream));
+}
+
+int svg_sparse_attn_fp8_fwd(const svg_shape_t* shape, const void* q8, const void* k8,
+                            const void* v8t, const float* scales, void* o, const uint8_t* labels,
+                            const int32_t* row_ptr_s, const int32_t* col_idx_s,
+                            const int32_t* row_ptr_t, const int32_t* col_idx_t, void* stream) {
+  Geo g;
+  int rc = svg::make_geo(shape, &g);
+  if (rc != SVG_OK) return rc;
+  if (g.D != 128 || g.bm != 128) return SVG_ERR_UNSUPPORTED;
+  if (!scales || svg::misaligned16(scales)) return SVG_ERR_INVALID_ARG;
+  rc = check_qkvo(q8, k8, v8t, o);
+  if (rc != SVG_OK) return rc;
+  if (!row_ptr_s || !col_idx_s) return SVG_ERR_INVALID_ARG;
+  if (labels && (!row_ptr_t || !col_idx_t)) return SVG_ERR_INVALID_ARG;
+  return svg::launch_fp8_attention(g, q8, k8, v8t, scales, o, labels, row_ptr_s, col_idx_s, row_ptr_t,
+                                   col_idx_t, static_cast<hipStream_t>(stream));
+}
+
 }  // extern "C"

@@ -54,4 +54,10 @@ int launch_attention(const Geo& g, const void* q, const void* k, const void* v, 
 int launch_profile(const Geo& g, const void* q, const void* k, const void* v, const int32_t* rows,
                    int t, uint8_t* labels, float* mse, float* workspace, hipStream_t stream);
 
+int launch_fp8_quantize(const Geo& g, const void* q, const void* k, const void* v, const uint8_t* labels,
+                        void* q8, void* k8, void* v8t, float* scales, hipStream_t stream);
+int launch_fp8_attention(const Geo& g, const void* q8, const void* k8, const void* v8t, const float* scales,
+                         void* o, const uint8_t* labels, const int32_t* row_ptr_s, const int32_t* col_idx_s,
+                         const int32_t* row_ptr_t, const int32_t* col_idx_t, hipStream_t stream);
+
 }  // namespace svg

@@ -79,3 +79,63 @@ def labels_match(gpu_labels, oracle_mse, oracle_labels, rel=1e-3):
     hi = np.maximum(oracle_mse[..., 0], oracle_mse[..., 1])
     gap = np.abs(oracle_mse[..., 0] - oracle_mse[..., 1]) / np.where(hi > 0, hi, 1.0)
     return bool(((gl == oracle_labels) | (gap < rel)).all())
+
+
+# ----------------------------------------------------------------------------- FP8
+def gpu_fp8_quantize(shape, q, k, v, labels):
+    """Runs svg_fp8_quantize; returns (q8, k8, v8t, scales) device tensors."""
+    BH = shape.B * shape.H
+    nq, nk = S.svg_tile_counts(shape)
+    q8 = torch.empty(S.svg_fp8_buffer_bytes(shape, S.SVG_FP8_Q), dtype=torch.uint8, device="cuda")
+    k8 = torch.full((S.svg_fp8_buffer_bytes(shape, S.SVG_FP8_K),), 0xAA, dtype=torch.uint8, device="cuda")
+    v8t = torch.full((S.svg_fp8_buffer_bytes(shape, S.SVG_FP8_VT),), 0xAA, dtype=torch.uint8, device="cuda")
+    scales = torch.zeros(S.svg_fp8_buffer_bytes(shape, S.SVG_FP8_SCALES) // 4, dtype=torch.float32, device="cuda")
+    S.svg_fp8_quantize(shape, q, k, v, labels, q8, k8, v8t, scales)
+    torch.cuda.synchronize()
+    return q8, k8, v8t, scales
+
+
+def gpu_layer_fp8(shape, q, k, v, labels, lists=None):
+    """quantise (+ layout of k, v) -> FP8 block-sparse attention; returns o (token order)."""
+    lists = lists or device_tile_lists(shape)
+    q8, k8, v8t, scales = gpu_fp8_quantize(shape, q, k, v, labels)
+    o = torch.empty_like(q)
+    S.svg_sparse_attn_fp8_fwd(shape, q8, k8, v8t, scales, o, labels, *lists)
+    torch.cuda.synchronize()
+    return o
+
+
+def v8t_rows(v8t: np.ndarray, nk: int) -> np.ndarray:
+    """Undoes the tile-image arrangement of v8t for one head: uint8 [nk*8192] -> codes
+    [nk*64, 128].  An image is [half-wave g][channel d][32 key slots]; slot 4 j + c of g is
+    key 32 (j // 4) + 8 (j % 4) + 4 g + c of the tile; the two 16-byte halves of a channel
+    are swapped when bit 3 of d is set."""
+    img = v8t.reshape(nk, 2, 128, 2, 16)
+    d = np.arange(128)
+    sw = (d >> 3) & 1
+    slots = np.empty((nk, 2, 128, 32), np.uint8)
+    for h in (0, 1):
+        slots[:, :, d, 16 * h:16 * h + 16] = img[:, :, d, h ^ sw, :]
+    rows = np.empty((nk, 64, 128), np.uint8)
+    for g in (0, 1):
+        for i in range(32):
+            j, c = i >> 2, i & 3
+            rows[:, 32 * (j >> 2) + 8 * (j & 3) + 4 * g + c, :] = slots[:, g, :, i]
+    return rows.reshape(nk * 64, 128)
+
+
+FP8_REL_RMS = 0.05      # FP8 attention vs the oracle over the same quantised q, k, v
+
+
+def assert_fp8_attn_close(got: torch.Tensor, ref: np.ndarray, v_absmax: float, what=""):
+    """The kernel rounds every attention weight to E4M3 (3 mantissa bits, relative error at
+    most 2^-4, about 3.6 % rms) before the second product and normalises by the sum of the
+    rounded weights, so the output is a weighted mean of v rows with perturbed weights:
+    its error is at most 2 * 2^-4 / (1 - 2^-4) of the spread of v in the worst case and a
+    small fraction of that when the errors of many keys average out."""
+    g = f64(got)
+    assert np.isfinite(g).all(), f"{what}: non-finite output"
+    err = np.abs(g - ref)
+    assert err.max() <= 2.0 ** -4 * v_absmax + 1e-2, f"{what}: max-abs {err.max():.4g}"
+    rel = np.linalg.norm(g - ref) / max(np.linalg.norm(ref), 1e-30)
+    assert rel <= FP8_REL_RMS, f"{what}: relative rms error {rel:.4g}"
