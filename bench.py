@@ -23,6 +23,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 PEAK_BF16_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
+PEAK_FP8_TFLOPS = 5000.0      # MI355X dense fp8 MFMA peak
 PEAK_HBM_GBS = 8000.0
 
 
@@ -44,6 +45,9 @@ def parse():
     ap.add_argument("--four-layout-passes", action="store_true",
                     help="time the pipeline with q, k, v and o all going through the layout kernels, instead of "
                          "the default where the attention kernel gathers q rows and scatters o rows itself")
+    ap.add_argument("--no-fp8", action="store_true",
+                    help="skip the FP8 variant of the sparse pass (Sec. 4.3 Quantization; head dimension 128 only), "
+                         "which is otherwise timed beside the bf16 pipeline and reported in the 'fp8' object")
     ap.add_argument("--only", default="", help="time a single stage only (profile|layout|sparse|dense); "
                     "used for per-kernel rocprofv3 runs")
     return ap.parse_args()
@@ -276,6 +280,52 @@ def main():
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic, "counters": counters},
     }
+    if not args.no_fp8 and S.svg_fp8_buffer_bytes(sh, S.SVG_FP8_Q) > 0:
+        # the same layer with the sparse pass in FP8: profiling as above (bf16), one quantisation pass
+        # (per-head maxima, conversion, layout of k and v of temporal heads), FP8 attention
+        f8 = [torch.empty(S.svg_fp8_buffer_bytes(sh, w), dtype=torch.uint8, device="cuda") for w in range(3)]
+        f8s = torch.zeros(S.svg_fp8_buffer_bytes(sh, S.SVG_FP8_SCALES) // 4, dtype=torch.float32, device="cuda")
+        o8 = torch.empty_like(q)
+
+        def fp8_quantize():
+            S.svg_fp8_quantize(sh, q, k, v, labels, *f8, f8s)
+
+        def fp8_attn():
+            S.svg_sparse_attn_fp8_fwd(sh, *f8, f8s, o8, labels, *lists)
+
+        times = {}
+        for name, fn in (("quantize", fp8_quantize), ("sparse_attn", fp8_attn)):
+            for _ in range(max(1, args.warmup)):
+                fn()
+            torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            times[name] = e0.elapsed_time(e1) / args.steps
+        if folded:
+            diff = (o8.float() - o.float()).norm().item() / max(o.float().norm().item(), 1e-30)
+        else:
+            diff = None
+        layer8 = breakdown["profile"] + times["quantize"] + times["sparse_attn"]
+        tf8 = tile_flops * nnz_total / (times["sparse_attn"] * 1e-3) / 1e12
+        out["fp8"] = {
+            "format": "E4M3, one scale per head and tensor; attention weights E4M3; fp32 accumulation",
+            "breakdown_ms": {"profile": breakdown["profile"], "quantize_and_layout": times["quantize"],
+                             "sparse_attn": times["sparse_attn"]},
+            "ms_per_layer": layer8,
+            "effective_tflops": dense_flops / (layer8 * 1e-3) / 1e12,
+            "speedup_vs_bf16_layer": wall_ms / layer8,
+            "speedup_vs_bf16_sparse_kernel": sparse_ms / times["sparse_attn"],
+            "speedup_vs_dense": None if dense_ms is None else dense_ms / layer8,
+            "roofline": {"kernel": "attn_fp8_kernel", "bound": "mfma", "achieved": tf8, "peak": PEAK_FP8_TFLOPS,
+                         "unit": "TFLOP/s", "frac": tf8 / PEAK_FP8_TFLOPS},
+            # bytes of the quantisation pass: q, k, v read twice (maxima, conversion), written once as bytes
+            "quantize_gbs": (2 * 3 * 2 + 3) * BH * N * D / (times["quantize"] * 1e-3) / 1e9,
+            "relative_difference_to_bf16_output": diff,
+        }
     if args.without_layout_transform:
         # same labels, same kernel, unpermuted q, k, v: the temporal slot gets the list of the
         # temporal mask in frame-major order
