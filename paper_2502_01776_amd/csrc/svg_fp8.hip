@@ -418,7 +418,9 @@ __global__ __launch_bounds__(256, 2) void attn_fp8_kernel(Fp8Args a) {
 #pragma unroll
       for (int c = 0; c < 4; ++c)
         p[c] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[j >> 2][4 * (j & 3) + c], c_log2, -mc));
-      int w = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], 0, false);
+      // (the first conversion writes the low half of its destination and keeps the rest: giving it
+      // a value that dies here as the "rest" saves a register clear; the second one fills the high half)
+      int w = __builtin_amdgcn_cvt_pk_fp8_f32(p[0], p[1], (int)__float_as_uint(p[0]), false);
       pb[j] = __builtin_amdgcn_cvt_pk_fp8_f32(p[2], p[3], w, true);
     }
 

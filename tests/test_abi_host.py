@@ -198,6 +198,32 @@ def test_pointer_checks_without_gpu():
     assert lib.svg_profile_heads(C.byref(sh), a, a, a, None, 24, a, None, b, need, None) == -1
 
 
+def test_fp8_buffer_sizes_and_argument_checks_without_gpu():
+    lib = S.lib()
+    cfg = get_config("mid128")
+    sh = S.shape_from_config(cfg)
+    nq, nk = S.svg_tile_counts(sh)
+    bh = sh.B * sh.H
+    assert S.svg_fp8_buffer_bytes(sh, S.SVG_FP8_Q) == bh * cfg["N"] * 128
+    assert S.svg_fp8_buffer_bytes(sh, S.SVG_FP8_K) == S.svg_fp8_buffer_bytes(sh, S.SVG_FP8_VT) == bh * nk * 64 * 128
+    assert S.svg_fp8_buffer_bytes(sh, S.SVG_FP8_SCALES) == 6 * bh * 4
+    assert S.svg_fp8_buffer_bytes(sh, 7) == 0
+    a = 0x10000000
+    # head dimension 64 and the small tile shape are not supported by the FP8 path
+    for name in ("mid64", "tiny"):
+        bad = S.shape_from_config(get_config(name))
+        assert S.svg_fp8_buffer_bytes(bad, S.SVG_FP8_Q) == 0
+        assert lib.svg_fp8_quantize(C.byref(bad), a, a, a, None, a, a, a, a, None) == -2
+        assert lib.svg_sparse_attn_fp8_fwd(C.byref(bad), a, a, a, a, a, None, a, a, None, None, None) == -2
+    # NULL / misaligned pointers are rejected before any launch
+    assert lib.svg_fp8_quantize(C.byref(sh), a, a, None, None, a, a, a, a, None) == -1
+    assert lib.svg_fp8_quantize(C.byref(sh), a, a, a, None, a, a + 4, a, a, None) == -1
+    assert lib.svg_fp8_quantize(C.byref(sh), a, a, a, None, a, a, a, None, None) == -1
+    assert lib.svg_sparse_attn_fp8_fwd(C.byref(sh), a, a, a, None, a, None, a, a, None, None, None) == -1
+    assert lib.svg_sparse_attn_fp8_fwd(C.byref(sh), a, a, a, a, a, None, None, a, None, None, None) == -1
+    assert lib.svg_sparse_attn_fp8_fwd(C.byref(sh), a, a, a, a, a, a, a, a, None, None, None) == -1
+
+
 def test_product_package_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2502_01776_amd")
     for dirpath, _, files in os.walk(pkg):
