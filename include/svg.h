@@ -185,8 +185,8 @@ int svg_dense_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, c
  * FP8 attention (Sec. 4.3 "Quantization", Sec. 5.2: FP8 quantisation of the sparse
  * attention, applied at head dimension 128).  The paper names no format or scaling;
  * this library uses OCP E4M3 (largest finite value 448) with one scale per head and
- * tensor, scale = max|x| / 448 (1 for an all-zero head), x ~ code * scale, codes rounded
- * to nearest even in float32.  Head dimension 128 and 128 x 64 tiles only, otherwise
+ * tensor, scale = max|x| / 448 (1 for an all-zero head), x ~ code * scale, code = nearest
+ * even of x * (1 / scale) with scale, reciprocal and product in float32.  Head dimension 128 and 128 x 64 tiles only, otherwise
  * SVG_ERR_UNSUPPORTED.
  *
  * svg_fp8_quantize converts q, k, v (device bf16 [B,H,N,128], token order) into

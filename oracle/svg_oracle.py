@@ -289,9 +289,9 @@ def svg_attention_layer(q, k, v, labels, g: Geometry):
 # Reading (the paper only says that FP8 quantisation is applied to the sparse attention and
 # names no format or scaling): the OCP 8-bit format E4M3 (1 sign, 4 exponent bits with bias 7,
 # 3 mantissa bits, subnormals, largest finite value 448, no infinities) with one scale per
-# head and tensor, scale = max|x| / 448, round to nearest even.  The decisions that produce
-# the integer codes (the scale, the division by it, the rounding) are taken in float32, the
-# precision the kernel takes them in; everything after the codes is float64.  The oracle
+# head and tensor, scale = max|x| / 448, code = nearest even of x * (1 / scale).  The decisions
+# that produce the integer codes (the scale, its reciprocal, the product, the rounding) are taken
+# in float32, the precision the kernel takes them in; everything after the codes is float64.  The oracle
 # defines the result as exact attention over the DEQUANTISED tensors; that the kernel also
 # rounds the attention weights to E4M3 before the second product is covered by the tolerance.
 # ----------------------------------------------------------------------------
@@ -335,7 +335,8 @@ def fp8_quantize_head(x):
     x32 = np.asarray(x, dtype=np.float32)
     amax = np.float32(np.max(np.abs(x32))) if x32.size else np.float32(0)
     scale = np.float32(amax / np.float32(E4M3_MAX)) if amax > 0 else np.float32(1)
-    return e4m3_encode(x32 / scale), scale
+    inv = np.float32(1) / scale
+    return e4m3_encode(x32 * inv), scale
 
 
 def fp8_dequantize(codes, scale) -> np.ndarray:

@@ -110,6 +110,7 @@ __global__ __launch_bounds__(256) void fp8_quantize_kernel(QuantArgs a) {
   const float amax = __uint_as_float(a.amax[tensor * a.BH + bh]);
   const float scale = amax > 0.f ? amax / kE4M3Max : 1.0f;
   if (tile == 0 && tid == 0) a.scales[tensor * a.BH + bh] = scale;
+  const float inv_scale = 1.0f / scale;      // codes = nearest even of x * (1 / scale), both in fp32
   // k and v of temporal heads are written in P-outer order: row m holds token off + f P + p
   // with m = off + p F + f (Sec. 4.2); q stays in token order (the attention kernel gathers it)
   const bool permute = tensor != 0 && a.labels != nullptr && a.labels[bh] == SVG_HEAD_TEMPORAL;
@@ -142,7 +143,7 @@ __global__ __launch_bounds__(256) void fp8_quantize_kernel(QuantArgs a) {
       for (int e = 0; e < 4; ++e) {
         const unsigned word = x[2 * w + (e >> 1)];
         const float val = __uint_as_float((e & 1) ? (word & 0xffff0000u) : (word << 16));
-        y[e] = fminf(fmaxf(val / scale, -kE4M3Max), kE4M3Max);
+        y[e] = fminf(fmaxf(val * inv_scale, -kE4M3Max), kE4M3Max);
       }
       int pk = __builtin_amdgcn_cvt_pk_fp8_f32(y[0], y[1], 0, false);
       pk = __builtin_amdgcn_cvt_pk_fp8_f32(y[2], y[3], pk, true);
