@@ -356,3 +356,78 @@ def svg_attention_layer_fp8(q, k, v, labels, g: Geometry):
                 codes, scale = fp8_quantize_head(src[b, h])
                 dst[b, h] = fp8_dequantize(codes, scale)
     return svg_attention_layer(dq, dk, dv, labels, g)
+
+
+# ----------------------------------------------------------------------------
+# QK-norm and rotary position embedding (Sec. 4.3 "Efficient kernel customization", Table 2):
+# the two small per-token operations on q and k in front of the attention.
+#
+# Reading (the paper names the operations and gives no formula; these are the textbook
+# definitions the models it evaluates use):
+#   QK-norm  normalisation of every token's head vector x in R^D with a learned weight,
+#            RMS form      y = x / sqrt(mean(x^2) + eps) * w           (HunyuanVideo)
+#            LayerNorm     y = (x - mean(x)) / sqrt(var(x) + eps) * w + b, biased variance
+#                                                                       (CogVideoX)
+#   RoPE     every channel pair (a, b) of a VIDEO token is rotated by the angle the model's
+#            tables give for that token and pair: (a cos - b sin, b cos + a sin).  The tables
+#            cos, sin [F*P, D/2] are inputs (how a model fills them from its 3D positions is
+#            its own business).  Pairs are (x[2i], x[2i+1]) ("interleaved") or
+#            (x[i], x[i+D/2]) ("half").  Text tokens are not rotated.
+# QK-norm comes first, then RoPE.
+# ----------------------------------------------------------------------------
+NORM_NONE, NORM_RMS, NORM_LAYER = 0, 1, 2
+ROPE_INTERLEAVED, ROPE_HALF = 0, 1
+
+
+def qk_norm(x, kind: int, weight=None, bias=None, eps: float = 1e-6) -> np.ndarray:
+    """x [..., D] float64."""
+    x = np.asarray(x, dtype=np.float64)
+    if kind == NORM_NONE:
+        return x.copy()
+    if kind == NORM_RMS:
+        y = x / np.sqrt(np.mean(x * x, axis=-1, keepdims=True) + eps)
+    elif kind == NORM_LAYER:
+        mu = np.mean(x, axis=-1, keepdims=True)
+        var = np.mean((x - mu) ** 2, axis=-1, keepdims=True)
+        y = (x - mu) / np.sqrt(var + eps)
+    else:
+        raise ValueError(kind)
+    if weight is not None:
+        y = y * np.asarray(weight, dtype=np.float64)
+    if bias is not None and kind == NORM_LAYER:
+        y = y + np.asarray(bias, dtype=np.float64)
+    return y
+
+
+def rope(x, cos, sin, g: Geometry, pairing: int = ROPE_INTERLEAVED) -> np.ndarray:
+    """x [N, D] float64 of one head in the original token order; cos, sin [F*P, D/2]."""
+    x = np.asarray(x, dtype=np.float64)
+    out = x.copy()
+    D = x.shape[-1]
+    vid = slice(g.off, g.off + g.F * g.P)
+    xv = x[vid]
+    if pairing == ROPE_INTERLEAVED:
+        a, b = xv[:, 0::2], xv[:, 1::2]
+    else:
+        a, b = xv[:, :D // 2], xv[:, D // 2:]
+    ra = a * cos - b * sin
+    rb = b * cos + a * sin
+    yv = np.empty_like(xv)
+    if pairing == ROPE_INTERLEAVED:
+        yv[:, 0::2], yv[:, 1::2] = ra, rb
+    else:
+        yv[:, :D // 2], yv[:, D // 2:] = ra, rb
+    out[vid] = yv
+    return out
+
+
+def qk_norm_rope(x, g: Geometry, kind=NORM_NONE, weight=None, bias=None, eps=1e-6, cos=None, sin=None,
+                 pairing=ROPE_INTERLEAVED) -> np.ndarray:
+    """x [B,H,N,D] float64: QK-norm of every token, then RoPE of the video tokens (skipped when
+    no tables are given)."""
+    y = qk_norm(x, kind, weight, bias, eps)
+    if cos is not None:
+        for b in range(y.shape[0]):
+            for h in range(y.shape[1]):
+                y[b, h] = rope(y[b, h], cos, sin, g, pairing)
+    return y

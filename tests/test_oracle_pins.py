@@ -565,3 +565,86 @@ def test_fp8_layer_is_the_plain_layer_when_quantisation_is_lossless():
     a, b = O.svg_attention_layer_fp8(q, k, v, labels, g), O.svg_attention_layer(q, k, v, labels, g)
     rel = np.linalg.norm(a - b) / np.linalg.norm(b)
     assert 1e-4 < rel < 0.1
+
+
+# ----------------------------------------------------------------------------- QK-norm, RoPE
+def test_qk_norm_against_library_and_closed_forms():
+    rng = np.random.default_rng(3)
+    x = rng.normal(0.3, 1.7, (5, 7, 64))
+    w, b = rng.normal(1, 0.2, 64), rng.normal(0, 0.2, 64)
+    ref = torch.nn.functional.layer_norm(torch.from_numpy(x), (64,), torch.from_numpy(w), torch.from_numpy(b), eps=1e-6)
+    assert np.allclose(O.qk_norm(x, O.NORM_LAYER, w, b, 1e-6), ref.numpy(), rtol=1e-12, atol=1e-12)
+    # RMS form: hand-worked (3, 4) -> rms = sqrt(12.5); unit rms output; invariant to the input's scale
+    assert np.allclose(O.qk_norm(np.array([3.0, 4.0]), O.NORM_RMS, None, None, 0.0), np.array([3.0, 4.0]) / math.sqrt(12.5))
+    y = O.qk_norm(x, O.NORM_RMS, None, None, 0.0)
+    assert np.allclose(np.sqrt((y * y).mean(-1)), 1.0)
+    assert np.allclose(O.qk_norm(7.5 * x, O.NORM_RMS, w, None, 0.0), O.qk_norm(x, O.NORM_RMS, w, None, 0.0))
+    assert np.allclose(O.qk_norm(x, O.NORM_RMS, w, None, 0.0), y * w)
+    # eps enters under the root: a zero vector stays zero instead of dividing by zero
+    assert not O.qk_norm(np.zeros(8), O.NORM_RMS, None, None, 1e-6).any()
+    # the RMS form does not centre, LayerNorm does
+    assert abs(O.qk_norm(x, O.NORM_LAYER, None, None, 0.0).mean(-1)).max() < 1e-12 < abs(y.mean(-1)).max()
+    assert np.array_equal(O.qk_norm(x, O.NORM_NONE), x)
+
+
+def test_rope_is_a_complex_rotation_of_the_video_tokens():
+    cfg = get_config("tiny")
+    g = O.Geometry.from_config(cfg)
+    rng = np.random.default_rng(8)
+    x = rng.normal(0, 1, (g.N, g.D))
+    theta = rng.uniform(-3, 3, (g.F * g.P, g.D // 2))
+    y = O.rope(x, np.cos(theta), np.sin(theta), g, O.ROPE_INTERLEAVED)
+    vid = slice(g.off, g.off + g.F * g.P)
+    z = (x[vid, 0::2] + 1j * x[vid, 1::2]) * np.exp(1j * theta)       # the same thing in complex arithmetic
+    assert np.allclose(y[vid, 0::2], z.real) and np.allclose(y[vid, 1::2], z.imag)
+    text = np.ones(g.N, bool)
+    text[vid] = False
+    assert text.any() and np.array_equal(y[text], x[text])              # text tokens are not rotated
+    assert np.allclose((y ** 2).sum(-1), (x ** 2).sum(-1))              # rotations keep the norm
+    # rotating by a then b is rotating by a + b; rotating back restores x
+    t2 = rng.uniform(-3, 3, theta.shape)
+    y2 = O.rope(y, np.cos(t2), np.sin(t2), g)
+    assert np.allclose(y2, O.rope(x, np.cos(theta + t2), np.sin(theta + t2), g))
+    assert np.allclose(O.rope(y, np.cos(-theta), np.sin(-theta), g), x)
+    # hand-worked: a quarter turn maps (a, b) to (-b, a)
+    q = O.rope(x, np.zeros_like(theta), np.ones_like(theta), g)
+    assert np.allclose(q[vid, 0::2], -x[vid, 1::2]) and np.allclose(q[vid, 1::2], x[vid, 0::2])
+    # the "half" pairing is the interleaved one on a vector whose halves are interleaved
+    inter = np.empty_like(x)
+    inter[:, 0::2], inter[:, 1::2] = x[:, :g.D // 2], x[:, g.D // 2:]
+    yi = O.rope(inter, np.cos(theta), np.sin(theta), g, O.ROPE_INTERLEAVED)
+    yh = O.rope(x, np.cos(theta), np.sin(theta), g, O.ROPE_HALF)
+    assert np.allclose(yh[:, :g.D // 2], yi[:, 0::2]) and np.allclose(yh[:, g.D // 2:], yi[:, 1::2])
+
+
+def test_rope_scores_depend_on_relative_position_only():
+    """With angles proportional to a 1-D position the rotated dot product depends only on the
+    distance of the two tokens: the property the embedding exists for."""
+    g = O.Geometry(B=1, H=1, F=1, P=40, T=0, D=16)
+    rng = np.random.default_rng(12)
+    qv, kv = rng.normal(0, 1, 16), rng.normal(0, 1, 16)
+    freq = 1.0 / 100.0 ** (np.arange(8) / 8.0)
+    theta = np.arange(40)[:, None] * freq[None, :]
+    rq = O.rope(np.tile(qv, (40, 1)), np.cos(theta), np.sin(theta), g)
+    rk = O.rope(np.tile(kv, (40, 1)), np.cos(theta), np.sin(theta), g)
+    s = rq @ rk.T
+    for d in (0, 1, 5, 17):
+        diag = np.array([s[m, m + d] for m in range(40 - d)])
+        assert np.allclose(diag, diag[0])
+    assert not np.allclose(s[0, 1], s[0, 2])
+
+
+def test_qk_norm_rope_composition_order():
+    cfg = get_config("tiny")
+    g = O.Geometry.from_config(cfg)
+    rng = np.random.default_rng(14)
+    x = rng.normal(0, 1, (g.B, g.H, g.N, g.D))
+    w, b = rng.normal(1, 0.3, g.D), rng.normal(0, 0.3, g.D)
+    theta = rng.uniform(-3, 3, (g.F * g.P, g.D // 2))
+    y = O.qk_norm_rope(x, g, O.NORM_LAYER, w, b, 1e-6, np.cos(theta), np.sin(theta))
+    want = O.rope(O.qk_norm(x[0, 1], O.NORM_LAYER, w, b, 1e-6), np.cos(theta), np.sin(theta), g)
+    assert np.allclose(y[0, 1], want)
+    # the weight makes the two steps not commute, so the order is observable
+    other = O.qk_norm(O.rope(x[0, 1], np.cos(theta), np.sin(theta), g), O.NORM_LAYER, w, b, 1e-6)
+    assert not np.allclose(want, other)
+    assert np.allclose(O.qk_norm_rope(x, g, O.NORM_RMS, w), O.qk_norm(x, O.NORM_RMS, w))
