@@ -48,6 +48,9 @@ def parse():
     ap.add_argument("--no-fp8", action="store_true",
                     help="skip the FP8 variant of the sparse pass (Sec. 4.3 Quantization; head dimension 128 only), "
                          "which is otherwise timed beside the bf16 pipeline and reported in the 'fp8' object")
+    ap.add_argument("--no-qk-norm-rope", action="store_true",
+                    help="skip the timing of the fused QK-norm + rotary embedding pass on q and k (Table 2), "
+                         "otherwise reported in the 'qk_norm_rope' object beside a plain PyTorch version")
     ap.add_argument("--only", default="", help="time a single stage only (profile|layout|sparse|dense); "
                     "used for per-kernel rocprofv3 runs")
     return ap.parse_args()
@@ -325,6 +328,60 @@ def main():
             # bytes of the quantisation pass: q, k, v read twice (maxima, conversion), written once as bytes
             "quantize_gbs": (2 * 3 * 2 + 3) * BH * N * D / (times["quantize"] * 1e-3) / 1e9,
             "relative_difference_to_bf16_output": diff,
+        }
+    if not args.no_qk_norm_rope:
+        # the two small per-token operations in front of the attention (Sec. 4.3, Table 2), fused into one
+        # pass per tensor: RMS form for the D = 128 models, LayerNorm form for the D = 64 ones
+        norm = S.SVG_NORM_RMS if D == 128 else S.SVG_NORM_LAYER
+        gen = torch.Generator(device="cuda").manual_seed(7)
+        wgt = 1.0 + 0.1 * torch.randn(D, generator=gen, device="cuda")
+        bia = 0.1 * torch.randn(D, generator=gen, device="cuda")
+        nv = cfg["F"] * cfg["P"]
+        freq = 1.0 / 10000.0 ** (torch.arange(D // 2, device="cuda", dtype=torch.float32) / (D // 2))
+        theta = torch.arange(nv, device="cuda", dtype=torch.float32)[:, None] * freq[None, :]
+        cos_t, sin_t = torch.cos(theta).contiguous(), torch.sin(theta).contiguous()
+        yq = qp        # scratch outputs (the timed pipeline is over)
+
+        def fused():
+            S.svg_qk_norm_rope(sh, q, yq, norm, wgt, bia, 1e-6, cos_t, sin_t, S.SVG_ROPE_INTERLEAVED)
+            S.svg_qk_norm_rope(sh, k, kp, norm, wgt, bia, 1e-6, cos_t, sin_t, S.SVG_ROPE_INTERLEAVED)
+
+        off = cfg["T"] if cfg["text_first"] else 0
+
+        def plain_torch(x):
+            xf = x.float()
+            if norm == S.SVG_NORM_RMS:
+                xf = xf * torch.rsqrt(xf.pow(2).mean(-1, keepdim=True) + 1e-6) * wgt
+            else:
+                xf = torch.nn.functional.layer_norm(xf, (D,), wgt, bia, 1e-6)
+            v = xf[:, :, off:off + nv].unflatten(-1, (D // 2, 2))
+            a_, b_ = v[..., 0], v[..., 1]
+            rot = torch.stack((a_ * cos_t - b_ * sin_t, b_ * cos_t + a_ * sin_t), dim=-1).flatten(-2)
+            xf[:, :, off:off + nv] = rot
+            return xf.to(torch.bfloat16)
+
+        def timed(fn, reps):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            for _ in range(reps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            return e0.elapsed_time(e1) / reps
+
+        ms_fused = timed(fused, args.steps)
+        ms_torch = timed(lambda: (plain_torch(q), plain_torch(k)), 3)
+        same = bool(((plain_torch(q).float() - yq.float()).abs() <= 2.0 ** -7 * yq.float().abs() + 1e-3).all())
+        moved = 2 * 2.0 * BH * N * D * 2 + 2 * nv * (D // 2) * 4        # q and k read + written, tables once
+        out["qk_norm_rope"] = {
+            "what": "%s QK-norm + interleaved RoPE of q and k, one fused pass per tensor" %
+                    ("RMS" if norm == S.SVG_NORM_RMS else "LayerNorm"),
+            "ms_q_and_k": ms_fused, "plain_pytorch_ms": ms_torch, "speedup_vs_plain_pytorch": ms_torch / ms_fused,
+            "matches_plain_pytorch": same,
+            "roofline": {"kernel": "norm_rope_kernel<%d>" % D, "bound": "hbm", "achieved": moved / (ms_fused * 1e-3) / 1e9,
+                         "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": moved / (ms_fused * 1e-3) / 1e9 / PEAK_HBM_GBS},
         }
     if args.without_layout_transform:
         # same labels, same kernel, unpermuted q, k, v: the temporal slot gets the list of the

@@ -182,6 +182,29 @@ int svg_dense_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, c
                        void* o, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * QK-norm and rotary position embedding of one tensor (q or k) in one pass: the two small
+ * per-token operations in front of the attention that the paper customises for small head
+ * dimensions (Sec. 4.3 "Efficient kernel customization", Table 2).  The paper gives no
+ * formulas; these are the definitions of the models it evaluates:
+ *   norm     SVG_NORM_NONE, SVG_NORM_RMS  y = x / sqrt(mean(x^2) + eps) * weight, or
+ *            SVG_NORM_LAYER  y = (x - mean) / sqrt(var + eps) * weight + bias (biased
+ *            variance), per token over the D channels of a head; weight, bias device
+ *            float [D], NULL means 1 and 0
+ *   rotation cos, sin device float [F*P, D/2], one row per VIDEO token in token order (both
+ *            NULL: no rotation); channel pair i of video token v becomes
+ *            (a cos[v,i] - b sin[v,i], b cos[v,i] + a sin[v,i]) with (a, b) = (x[2i], x[2i+1])
+ *            for SVG_ROPE_INTERLEAVED and (x[i], x[i+D/2]) for SVG_ROPE_HALF; text tokens
+ *            are not rotated.  The norm is applied first.
+ *   x, y     device bf16 [B,H,N,D], token order; y == x (in place) is allowed, any other
+ *            overlap is SVG_ERR_ALIAS.  Arithmetic in fp32, output rounded to bf16.
+ */
+enum { SVG_NORM_NONE = 0, SVG_NORM_RMS = 1, SVG_NORM_LAYER = 2 };
+enum { SVG_ROPE_INTERLEAVED = 0, SVG_ROPE_HALF = 1 };
+int svg_qk_norm_rope(const svg_shape_t* shape, const void* x, void* y, int norm, const float* weight,
+                     const float* bias, float eps, const float* cos, const float* sin, int pairing,
+                     void* stream);
+
+/*
  * FP8 attention (Sec. 4.3 "Quantization", Sec. 5.2: FP8 quantisation of the sparse
  * attention, applied at head dimension 128).  The paper names no format or scaling;
  * this library uses OCP E4M3 (largest finite value 448) with one scale per head and

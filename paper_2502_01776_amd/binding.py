@@ -18,6 +18,8 @@ LIB_PATH = os.path.join(_HERE, "libsvg_gfx950.so")
 SVG_HEAD_SPATIAL = 0
 SVG_HEAD_TEMPORAL = 1
 SVG_LIST_TEMPORAL_FRAME_MAJOR = 2   # list pattern only: temporal mask without the layout transformation
+SVG_NORM_NONE, SVG_NORM_RMS, SVG_NORM_LAYER = 0, 1, 2           # svg_qk_norm_rope
+SVG_ROPE_INTERLEAVED, SVG_ROPE_HALF = 0, 1
 SVG_FP8_Q, SVG_FP8_K, SVG_FP8_VT, SVG_FP8_SCALES = 0, 1, 2, 3   # svg_fp8_buffer_bytes
 SVG_ATTN_QO_TOKEN_ORDER = 1          # svg_sparse_attn_fwd_ex: q read and o written in token order
 SVG_OK = 0
@@ -25,7 +27,7 @@ SVG_OK = 0
 EXPORTS = ("svg_strerror", "svg_version", "svg_last_hip_error", "svg_workspace_bytes", "svg_tile_counts",
            "svg_tile_list_build", "svg_profile_heads", "svg_layout_fwd", "svg_layout_inv",
            "svg_sparse_attn_fwd", "svg_sparse_attn_fwd_ex", "svg_dense_attn_fwd",
-           "svg_fp8_buffer_bytes", "svg_fp8_quantize", "svg_sparse_attn_fp8_fwd")
+           "svg_fp8_buffer_bytes", "svg_fp8_quantize", "svg_sparse_attn_fp8_fwd", "svg_qk_norm_rope")
 
 
 class SvgShape(C.Structure):
@@ -82,6 +84,8 @@ def lib():
         L.svg_sparse_attn_fwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.svg_sparse_attn_fwd_ex.restype = C.c_int
         L.svg_sparse_attn_fwd_ex.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_uint32, vp, C.c_size_t, vp]
+        L.svg_qk_norm_rope.restype = C.c_int
+        L.svg_qk_norm_rope.argtypes = [sp, vp, vp, C.c_int, vp, vp, C.c_float, vp, vp, C.c_int, vp]
         L.svg_fp8_buffer_bytes.restype = C.c_size_t
         L.svg_fp8_buffer_bytes.argtypes = [sp, C.c_int]
         L.svg_fp8_quantize.restype = C.c_int
@@ -211,3 +215,10 @@ def svg_sparse_attn_fp8_fwd(shape, q8, k8, v8t, scales, o, labels, row_ptr_s, co
                                          _ptr(o), _ptr(labels), _ptr(row_ptr_s), _ptr(col_idx_s),
                                          _ptr(row_ptr_t), _ptr(col_idx_t), _stream(stream)),
            "svg_sparse_attn_fp8_fwd")
+
+
+def svg_qk_norm_rope(shape, x, y, norm=SVG_NORM_NONE, weight=None, bias=None, eps=1e-6, cos=None, sin=None,
+                     pairing=SVG_ROPE_INTERLEAVED, stream=None):
+    _check(lib().svg_qk_norm_rope(C.byref(shape), _ptr(x), _ptr(y), int(norm), _ptr(weight), _ptr(bias),
+                                  float(eps), _ptr(cos), _ptr(sin), int(pairing), _stream(stream)),
+           "svg_qk_norm_rope")

@@ -104,6 +104,24 @@ int svg_dense_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, c
                                false, static_cast<hipStream_t>(stream));
 }
 
+int svg_qk_norm_rope(const svg_shape_t* shape, const void* x, void* y, int norm, const float* weight,
+                     const float* bias, float eps, const float* cos, const float* sin, int pairing,
+                     void* stream) {
+  Geo g;
+  int rc = svg::make_geo(shape, &g);
+  if (rc != SVG_OK) return rc;
+  if (!x || !y || svg::misaligned16(x) || svg::misaligned16(y)) return SVG_ERR_INVALID_ARG;
+  if (norm != SVG_NORM_NONE && norm != SVG_NORM_RMS && norm != SVG_NORM_LAYER) return SVG_ERR_INVALID_ARG;
+  if (pairing != SVG_ROPE_INTERLEAVED && pairing != SVG_ROPE_HALF) return SVG_ERR_INVALID_ARG;
+  if ((cos == nullptr) != (sin == nullptr)) return SVG_ERR_INVALID_ARG;
+  if (cos && (svg::misaligned16(cos) || svg::misaligned16(sin))) return SVG_ERR_INVALID_ARG;
+  if (!(eps >= 0.f)) return SVG_ERR_INVALID_ARG;
+  // in place (y == x) is fine, a partial overlap is not
+  if (x != y && overlap(x, y, tensor_bytes(g))) return SVG_ERR_ALIAS;
+  return svg::launch_norm_rope(g, x, y, norm, weight, bias, eps, cos, sin, pairing,
+                               static_cast<hipStream_t>(stream));
+}
+
 size_t svg_fp8_buffer_bytes(const svg_shape_t* shape, int which) {
   Geo g;
   if (svg::make_geo(shape, &g) != SVG_OK || g.D != 128 || g.bm != 128) return 0;

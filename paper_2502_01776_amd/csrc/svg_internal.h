@@ -54,6 +54,8 @@ int launch_attention(const Geo& g, const void* q, const void* k, const void* v, 
 int launch_profile(const Geo& g, const void* q, const void* k, const void* v, const int32_t* rows,
                    int t, uint8_t* labels, float* mse, float* workspace, hipStream_t stream);
 
+int launch_norm_rope(const Geo& g, const void* x, void* y, int norm, const float* weight, const float* bias,
+                     float eps, const float* cos, const float* sin, int pairing, hipStream_t stream);
 int launch_fp8_quantize(const Geo& g, const void* q, const void* k, const void* v, const uint8_t* labels,
                         void* q8, void* k8, void* v8t, float* scales, hipStream_t stream);
 int launch_fp8_attention(const Geo& g, const void* q8, const void* k8, const void* v8t, const float* scales,

@@ -224,6 +224,25 @@ def test_fp8_buffer_sizes_and_argument_checks_without_gpu():
     assert lib.svg_sparse_attn_fp8_fwd(C.byref(sh), a, a, a, a, a, a, a, a, None, None, None) == -1
 
 
+def test_qk_norm_rope_argument_checks_without_gpu():
+    lib = S.lib()
+    sh = S.shape_from_config(get_config("mid64"))
+    nbytes = sh.B * sh.H * sh.N * sh.D * 2
+    a, b, t = 0x10000000, 0x10000000 + 4 * nbytes, 0x70000000
+    f = C.c_float(1e-6)
+    call = lambda *args: lib.svg_qk_norm_rope(C.byref(sh), *args)
+    assert call(None, b, 1, None, None, f, None, None, 0, None) == -1
+    assert call(a, b + 2, 1, None, None, f, None, None, 0, None) == -1
+    assert call(a, b, 3, None, None, f, None, None, 0, None) == -1            # unknown norm
+    assert call(a, b, 1, None, None, f, t, t, 2, None) == -1                  # unknown pairing
+    assert call(a, b, 1, None, None, f, t, None, 0, None) == -1               # cos without sin
+    assert call(a, b, 1, None, None, f, t + 4, t, 0, None) == -1              # misaligned table
+    assert call(a, b, 1, None, None, C.c_float(-1.0), None, None, 0, None) == -1
+    assert call(a, a + 16, 1, None, None, f, None, None, 0, None) == -4       # partial overlap
+    bad = S.shape_from_config(dict(get_config("mid64"), D=96))
+    assert lib.svg_qk_norm_rope(C.byref(bad), a, b, 1, None, None, f, None, None, 0, None) == -2
+
+
 def test_product_package_does_not_import_the_oracle():
     pkg = os.path.join(ROOT, "paper_2502_01776_amd")
     for dirpath, _, files in os.walk(pkg):
