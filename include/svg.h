@@ -163,9 +163,16 @@ int svg_sparse_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, 
  * the kernel gathering the query rows of a temporal head's tile and scattering its
  * output rows through the permutation; only k and v of temporal heads must be in
  * P-outer order.  Results are bit-identical to svg_layout_fwd(q) ->
- * svg_sparse_attn_fwd -> svg_layout_inv(o).  Unknown flag bits: SVG_ERR_INVALID_ARG.
+ * svg_sparse_attn_fwd -> svg_layout_inv(o).
+ * SVG_ATTN_ELEMENT_MASK applies the element mask of the head's pattern (Sec. 3.1: frames
+ * within w_s of the query's frame for a spatial head, in-frame positions within w_t for a
+ * temporal head; text keys, text queries and, if set, the first-frame sink always kept)
+ * inside every visited tile, so that the result is attention under the exact mask
+ * instead of its block cover.  The tile list still decides which tiles are visited (with
+ * the lists of svg_tile_list_build no kept element is lost); temporal heads are expected in
+ * P-outer order as usual.  Unknown flag bits: SVG_ERR_INVALID_ARG.
  */
-enum { SVG_ATTN_QO_TOKEN_ORDER = 1 };
+enum { SVG_ATTN_QO_TOKEN_ORDER = 1, SVG_ATTN_ELEMENT_MASK = 2 };
 int svg_sparse_attn_fwd_ex(const svg_shape_t* shape, const void* q, const void* k, const void* v,
                            void* o, const uint8_t* labels, const int32_t* row_ptr_s,
                            const int32_t* col_idx_s, const int32_t* row_ptr_t,

@@ -65,7 +65,7 @@ int svg_sparse_attn_fwd_ex(const svg_shape_t* shape, const void* q, const void* 
                            size_t workspace_bytes, void* stream) {
   (void)workspace;
   (void)workspace_bytes;
-  if (flags & ~(uint32_t)SVG_ATTN_QO_TOKEN_ORDER) return SVG_ERR_INVALID_ARG;
+  if (flags & ~(uint32_t)(SVG_ATTN_QO_TOKEN_ORDER | SVG_ATTN_ELEMENT_MASK)) return SVG_ERR_INVALID_ARG;
   Geo g;
   int rc = svg::make_geo(shape, &g);
   if (rc != SVG_OK) return rc;
@@ -77,7 +77,7 @@ int svg_sparse_attn_fwd_ex(const svg_shape_t* shape, const void* q, const void* 
   if (overlap(o, q, bytes) || overlap(o, k, bytes) || overlap(o, v, bytes)) return SVG_ERR_ALIAS;
   return svg::launch_attention(g, q, k, v, o, labels, row_ptr_s, col_idx_s, row_ptr_t, col_idx_t,
                                true, (flags & SVG_ATTN_QO_TOKEN_ORDER) != 0,
-                               static_cast<hipStream_t>(stream));
+                               (flags & SVG_ATTN_ELEMENT_MASK) != 0, static_cast<hipStream_t>(stream));
 }
 
 int svg_sparse_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, const void* v,
@@ -101,7 +101,7 @@ int svg_dense_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, c
   const size_t bytes = tensor_bytes(g);
   if (overlap(o, q, bytes) || overlap(o, k, bytes) || overlap(o, v, bytes)) return SVG_ERR_ALIAS;
   return svg::launch_attention(g, q, k, v, o, nullptr, nullptr, nullptr, nullptr, nullptr, false,
-                               false, static_cast<hipStream_t>(stream));
+                               false, false, static_cast<hipStream_t>(stream));
 }
 
 int svg_qk_norm_rope(const svg_shape_t* shape, const void* x, void* y, int norm, const float* weight,

@@ -71,7 +71,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   // (head dimension 64: twice the products per barrier) walks the list in pairs: an entry
   // of the cursor is (128-key tile index) * 4 + (which 64-key halves of it are kept).
   constexpr int LT = BN == 128 ? 2 : 1;
-  static_assert(LT == 1 || MODE != kProfile, "profiling uses list-sized key tiles");
+  // kSparseExact is kSparse with the head's element mask applied inside every visited tile
+  constexpr bool SPARSE = MODE == kSparse || MODE == kSparseExact;
+  constexpr bool MASKABLE = MODE == kProfile || MODE == kSparseExact;
+  static_assert(LT == 1 || !MASKABLE, "the masked forms use list-sized key tiles");
   constexpr int DS = D / 16;             // k-steps of the first product
   constexpr int DB = D / 32;             // 32-row blocks of O^T
   constexpr int K_PIECES = BN * CPR;
@@ -100,10 +103,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   static_assert(!SPLIT || (V_UNITS < THREADS && K_THREADS % CPR == 0), "K staging threads must cover whole rows");
 
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE_BYTES];
-  __shared__ __attribute__((aligned(16))) int key_code[MODE == kProfile ? 2 * BN : 4];
+  __shared__ __attribute__((aligned(16))) int key_code[MASKABLE ? 2 * BN : 4];
   // profile: per staged tile {smallest coordinate code, largest, flags}; flags bit 0: some key
   // is kept by every query, bit 1: some key is out of range, bit 2: coordinates span a wrap
-  __shared__ int tile_info[MODE == kProfile ? 2 * 4 : 4];
+  __shared__ int tile_info[MASKABLE ? 2 * 4 : 4];
   __shared__ int wg_range[4];    // profile: min / max coordinate of the workgroup's rows
 
   // ======================================================================================
@@ -151,7 +154,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
 
   // profile: the unmasked pass needs no key codes, tile summaries or element masks (only the
   // ragged end of the sequence, handled like in the dense pass)
-  const bool masked = MODE == kProfile && __builtin_amdgcn_readfirstlane(variant) != 0;
+  const bool masked = MODE == kSparseExact || (MODE == kProfile && __builtin_amdgcn_readfirstlane(variant) != 0);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -208,12 +211,21 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   // sparse: this head's pattern; with q and o kept in token order, the row of a temporal
   // head that this lane reads and writes is the token whose transformed position is qrow
   // (Sec. 4.2: position off + p F + f holds token off + f P + p)
-  const int pat = MODE == kSparse && a.labels ? (a.labels[bh] != 0) : 0;
+  const int pat = SPARSE && a.labels ? (a.labels[bh] != 0) : 0;
   int io_row = qrow;
-  if (MODE == kSparse && a.qo_token_order && pat && qrow >= a.off && qrow < a.video_end) {
+  if (SPARSE && a.qo_token_order && pat && qrow >= a.off && qrow < a.video_end) {
     const int vq = qrow - a.off;
     const int p = vq / a.F;
     io_row = a.off + (vq - p * a.F) * a.P + p;
+  }
+  if (MODE == kSparseExact && qrow >= a.off && qrow < a.video_end) {
+    // element mask of the head's pattern in the order its tile list refers to: a spatial head
+    // compares frames (coordinate = row / P), a temporal head in P-outer order compares in-frame
+    // positions (coordinate = row / F); text queries keep the default window (everything)
+    const int cq = (qrow - a.off) / (pat ? a.F : a.P);
+    const int w = pat ? a.w_t : a.w_s;
+    win_lo = cq - w;
+    win_span = 2u * (unsigned)w;
   }
 
   bf16x8 qreg[DS];     // lane (g, r) holds Q[qrow][16 s + 8 g .. +8]
@@ -236,7 +248,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   const int32_t* cols = nullptr;
   int lj = 0, lend = 0;              // sparse: cursor and end in col_idx;  dense: counter and nk
   int lbeg = 0, lleft = 0;           // sparse: start of the list row, entries still to hand out
-  if (MODE == kSparse) {
+  if (SPARSE) {
     const int32_t* rp = a.row_ptr[pat];
     cols = a.col_idx[pat];
     lbeg = __builtin_amdgcn_readfirstlane(rp[grp]);
@@ -329,7 +341,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   asm volatile("" : "+v"(lane_zero));
   int pend0 = kNoTile, pend1 = kNoTile;
   auto fetch_begin = [&]() {
-    if (MODE == kSparse) {
+    if (SPARSE) {
       pend0 = lleft > 0 ? cols[lj + lane_zero] : kNoTile;
       if (LT == 2) {      // the entry after it: may be the upper half of the same 128-key tile
         const int lj1 = lj + 1 == lend ? lbeg : lj + 1;
@@ -338,7 +350,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     }
   };
   auto fetch_end = [&]() -> int {
-    if (MODE == kSparse) {
+    if (SPARSE) {
       if (lleft <= 0) return kNoTile;
       const int c = __builtin_amdgcn_readfirstlane(pend0);
       int taken = 1, entry = c;
@@ -479,15 +491,21 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
         if (V_UNITS % THREADS == 0 || u < V_UNITS) store_v_unit(vb, u / CPR, u % CPR, vst[i]);
       }
     }
-    if (MODE == kProfile && masked && tid < BN) {
+    if (MASKABLE && masked && tid < BN) {
       // per-key mask code: the key's frame (spatial) or in-frame position (temporal), or
       // "kept by every query" (text / sink key, unmasked pass), or "out of range"
       const int key = col * BN + tid;
       int code;
       if (key >= a.N) {
         code = kCodeDrop;
-      } else if (variant == 0 || key < a.off || key >= a.video_end) {
+      } else if ((MODE == kProfile && variant == 0) || key < a.off || key >= a.video_end) {
         code = kCodeKeep;
+      } else if (MODE == kSparseExact) {
+        const int vk = key - a.off;
+        const int hi = vk / (pat ? a.F : a.P);          // spatial: frame; P-outer temporal: position
+        code = hi;
+        const int fk = pat ? vk - hi * a.F : hi;          // the key's frame
+        if (a.sink && fk == 0) code = kCodeKeep;
       } else {
         const int vk = key - a.off;
         const int fk = vk / a.P;
@@ -507,7 +525,9 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
         const int first = __builtin_ctzll(coord_lanes), last = 63 - __builtin_clzll(coord_lanes);
         cmin = __builtin_amdgcn_readlane(code, first);
         cmax = __builtin_amdgcn_readlane(code, last);
-        if (variant == 2 && cmax - cmin != last - first) flags |= 4;    // wrapped: treat as mixed
+        // (positions in frame-major order wrap at frame ends; the coordinates of the exact
+        // sparse form never decrease, so first and last always bound them)
+        if (MODE == kProfile && variant == 2 && cmax - cmin != last - first) flags |= 4;    // wrapped: treat as mixed
       }
       if (tid == 0) {
         tile_info[buf * 4 + 0] = cmin;
@@ -565,8 +585,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     const int halves = LT == 1 ? 3 : (col & 3);
 
     // profile: does this wavefront need the tile at all, and does it need per-element masks?
-    bool skip = false, need_masks = MODE == kProfile && masked;
-    if (MODE == kProfile && masked) {
+    bool skip = false, need_masks = MASKABLE && masked;
+    if (MASKABLE && masked) {
       const int cmin = tile_info[buf * 4 + 0], cmax = tile_info[buf * 4 + 1], flags = tile_info[buf * 4 + 2];
       bool lane_all = (flags & 6) == 0, lane_none = (flags & 5) == 0;
       if (cmax >= cmin) {       // the tile has coordinate keys
@@ -588,7 +608,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
       // ---- S^T = K Q^T.  Operand reads run PF products ahead of their use (a rolling
       // window of PF operand registers), so after the first few the LDS latency is hidden
       // behind the MFMAs; the scheduling barriers pin the read / product interleave.
-      constexpr int PF = (MODE == kProfile || BN == 128) ? 2 : kPrefetch;   // (those forms are short of registers)
+      constexpr int PF = (MASKABLE || BN == 128) ? 2 : kPrefetch;   // (those forms are short of registers)
       constexpr int NS = KB * DS;          // operands of the first product, order (kb, s)
       constexpr int NV = KB * 2 * DB;      // operands of the second product, order (kb, kk, db)
       auto k_operand = [&](int i) -> bf16x8 {
@@ -623,7 +643,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
 
       __builtin_amdgcn_s_setprio(0);
       // ---- masking.  sacc[kb][4 i + jj] belongs to key  col*BN + 32 kb + 8 i + 4 g + jj.
-      if (MODE == kProfile && masked) {
+      if (MASKABLE && masked) {
         if (need_masks) {
 #pragma unroll
           for (int kb = 0; kb < KB; ++kb)
@@ -898,7 +918,7 @@ int dispatch(const Geo& g, const AttnArgs& a, int rows_total, hipStream_t stream
     if (g.D == 128) return launch_one<128, 4, 64, MODE>(a, rows_total, stream);
     // head dimension 64: half the products per key, so the dense and sparse passes take
     // 128 keys per barrier (the tile list still counts 64-key tiles)
-    if constexpr (MODE == kProfile) return launch_one<64, 4, 64, MODE>(a, rows_total, stream);
+    if constexpr (MODE == kProfile || MODE == kSparseExact) return launch_one<64, 4, 64, MODE>(a, rows_total, stream);
     else return launch_one<64, 4, 128, MODE>(a, rows_total, stream);
   }
   return g.D == 128 ? launch_one<128, 1, 32, MODE>(a, rows_total, stream)
@@ -923,7 +943,7 @@ AttnArgs base_args(const Geo& g, const void* q, const void* k, const void* v, vo
 int launch_attention(const Geo& g, const void* q, const void* k, const void* v, void* o,
                      const uint8_t* labels, const int32_t* row_ptr_s, const int32_t* col_idx_s,
                      const int32_t* row_ptr_t, const int32_t* col_idx_t, bool sparse,
-                     bool qo_token_order, hipStream_t stream) {
+                     bool qo_token_order, bool element_mask, hipStream_t stream) {
   AttnArgs a = base_args(g, q, k, v, o);
   a.labels = labels;
   a.qo_token_order = sparse && qo_token_order ? 1 : 0;
@@ -931,6 +951,7 @@ int launch_attention(const Geo& g, const void* q, const void* k, const void* v, 
   a.row_ptr[1] = row_ptr_t; a.col_idx[1] = col_idx_t;
   // query tiles holding text rows keep every key tile: start them first
   a.reverse_q = (sparse && g.T > 0 && !g.text_first) ? 1 : 0;
+  if (sparse && element_mask) return dispatch<kSparseExact>(g, a, g.N, stream);
   return sparse ? dispatch<kSparse>(g, a, g.N, stream) : dispatch<kDense>(g, a, g.N, stream);
 }
 

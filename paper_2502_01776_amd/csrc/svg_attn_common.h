@@ -13,7 +13,7 @@ typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-enum Mode { kDense = 0, kSparse = 1, kProfile = 2 };
+enum Mode { kDense = 0, kSparse = 1, kProfile = 2, kSparseExact = 3 };
 
 constexpr int kCodeDrop = 0x7fffffff;   // key beyond N: never kept
 constexpr int kCodeKeep = 0x7ffffffe;   // text key / sink key: kept by every query

@@ -50,7 +50,7 @@ int launch_layout(const Geo& g, const void* in, void* out, const uint8_t* labels
 int launch_attention(const Geo& g, const void* q, const void* k, const void* v, void* o,
                      const uint8_t* labels, const int32_t* row_ptr_s, const int32_t* col_idx_s,
                      const int32_t* row_ptr_t, const int32_t* col_idx_t, bool sparse,
-                     bool qo_token_order, hipStream_t stream);
+                     bool qo_token_order, bool element_mask, hipStream_t stream);
 int launch_profile(const Geo& g, const void* q, const void* k, const void* v, const int32_t* rows,
                    int t, uint8_t* labels, float* mse, float* workspace, hipStream_t stream);
 

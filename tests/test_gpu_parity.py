@@ -274,7 +274,7 @@ def test_extended_entry_point_rejects_unknown_flags():
     o = torch.empty_like(q)
     lists = device_tile_lists(sh)
     with pytest.raises(S.SvgError):
-        S.svg_sparse_attn_fwd_ex(sh, q, k, v, o, None, *lists, flags=2)
+        S.svg_sparse_attn_fwd_ex(sh, q, k, v, o, None, *lists, flags=4)
     # flags == 0 is the plain entry point
     o0 = torch.empty_like(q)
     S.svg_sparse_attn_fwd_ex(sh, q, k, v, o, None, *lists, flags=0)
@@ -373,3 +373,65 @@ def test_large_logits_do_not_overflow():
     torch.cuda.synchronize()
     ref = O.dense_attention_head(f64(q)[0, 1], f64(k)[0, 1], f64(v)[0, 1], g)
     assert_attn_close(o[0, 1], ref, "boost 60")
+
+
+# ------------------------------------------------------------------ exact element mask
+@pytest.mark.parametrize("name", SMALL)
+@pytest.mark.parametrize("sink", [0, 1])
+def test_sparse_attention_with_element_mask(name, sink):
+    """SVG_ATTN_ELEMENT_MASK: attention under the exact masks of Sec. 3.1 (not their block cover),
+    against the oracle's masked attention in the original token order."""
+    cfg, sh, g = setup(name, sink_first_frame=sink)
+    q, k, v = make_qkv(cfg)
+    qc, kc, vc = q.cuda(), k.cuda(), v.cuda()
+    lab_np = planted_labels(cfg)
+    labels = torch.from_numpy(lab_np).cuda()
+    lists = device_tile_lists(sh)
+    kp, vp, o = (torch.empty_like(qc) for _ in range(3))
+    S.svg_layout_fwd(sh, kc, kp, labels)
+    S.svg_layout_fwd(sh, vc, vp, labels)
+    S.svg_sparse_attn_fwd_ex(sh, qc, kp, vp, o, labels, *lists,
+                             flags=S.SVG_ATTN_QO_TOKEN_ORDER | S.SVG_ATTN_ELEMENT_MASK)
+    torch.cuda.synchronize()
+    masks = {O.SPATIAL: O.spatial_mask(g), O.TEMPORAL: O.temporal_mask(g)}
+    qd, kd, vd = f64(q), f64(k), f64(v)
+    differs = False
+    block = gpu_layer_token_order(sh, qc, kc, vc, labels, lists)
+    for b in range(g.B):
+        for h in range(g.H):
+            ref = O.masked_attention(qd[b, h], kd[b, h], vd[b, h], masks[int(lab_np[b * g.H + h])], g.scale)
+            assert_attn_close(o[b, h], ref, f"{name} exact mask b{b} h{h}")
+            differs |= not torch.equal(o[b, h], block[b, h])
+    assert differs        # the block cover keeps more than the element mask on these shapes
+    # the four-pass pipeline with the flag gives the same bits
+    qp, op, o4 = (torch.empty_like(qc) for _ in range(3))
+    S.svg_layout_fwd(sh, qc, qp, labels)
+    S.svg_sparse_attn_fwd_ex(sh, qp, kp, vp, op, labels, *lists, flags=S.SVG_ATTN_ELEMENT_MASK)
+    S.svg_layout_inv(sh, op, o4, labels)
+    torch.cuda.synchronize()
+    assert torch.equal(o.view(torch.int16), o4.view(torch.int16))
+
+
+def test_element_mask_random_geometries():
+    rng = np.random.default_rng(777)
+    for case in range(10):
+        F, P = int(rng.integers(1, 8)), int(rng.integers(1, 260))
+        T = int(rng.choice([0, 1, 17, 64, 130]))
+        bm, bn = ((128, 64), (32, 32))[int(rng.integers(2))]
+        cfg = dict(get_config("mid64"), B=1, H=2, F=F, P=P, T=T, D=int(rng.choice([64, 128])),
+                   text_first=int(rng.integers(2)), w_s=int(rng.integers(0, F + 1)), w_t=int(rng.integers(0, P + 1)),
+                   sink_first_frame=int(rng.integers(2)), block_m=bm, block_n=bn, spatial_heads=[0])
+        cfg["N"] = F * P + T
+        sh, g = S.shape_from_config(cfg), O.Geometry.from_config(cfg)
+        q, k, v = make_plain_qkv(1, 2, g.N, g.D, seed=300 + case)
+        qc, kc, vc = q.cuda(), k.cuda(), v.cuda()
+        lab = torch.tensor([0, 1], dtype=torch.uint8, device="cuda")
+        kp, vp, o = (torch.empty_like(qc) for _ in range(3))
+        S.svg_layout_fwd(sh, kc, kp, lab)
+        S.svg_layout_fwd(sh, vc, vp, lab)
+        S.svg_sparse_attn_fwd_ex(sh, qc, kp, vp, o, lab, *device_tile_lists(sh),
+                                 flags=S.SVG_ATTN_QO_TOKEN_ORDER | S.SVG_ATTN_ELEMENT_MASK)
+        torch.cuda.synchronize()
+        for h, mask in ((0, O.spatial_mask(g)), (1, O.temporal_mask(g))):
+            ref = O.masked_attention(f64(q)[0, h], f64(k)[0, h], f64(v)[0, h], mask, g.scale)
+            assert_attn_close(o[0, h], ref, f"case {case} {cfg} head {h}")
