@@ -244,6 +244,7 @@ def main():
     # same command (not measured live): bytes past L2 per launch, and the fraction of shader
     # cycles with the MFMA unit busy together with the shader clock those cycles ran at
     traffic = counters = None
+    prof = {}
     tpath = os.path.join(ROOT, "profiles", f"hbm_traffic_{args.workload}.json")
     if os.path.exists(tpath):
         with open(tpath) as f:
@@ -324,7 +325,11 @@ def main():
             "speedup_vs_bf16_sparse_kernel": sparse_ms / times["sparse_attn"],
             "speedup_vs_dense": None if dense_ms is None else dense_ms / layer8,
             "roofline": {"kernel": "attn_fp8_kernel", "bound": "mfma", "achieved": tf8, "peak": PEAK_FP8_TFLOPS,
-                         "unit": "TFLOP/s", "frac": tf8 / PEAK_FP8_TFLOPS},
+                         "unit": "TFLOP/s", "frac": tf8 / PEAK_FP8_TFLOPS,
+                         "traffic": prof.get("fp8_attn_bytes_per_launch"),
+                         "counters": None if "fp8_attn_mfma_busy_fraction_of_cycles" not in prof else {
+                             "mfma_busy_fraction_of_cycles": prof["fp8_attn_mfma_busy_fraction_of_cycles"],
+                             "shader_clock_ghz": prof["fp8_attn_shader_clock_ghz"], "source": prof.get("source")}},
             # bytes of the quantisation pass: q, k, v read twice (maxima, conversion), written once as bytes
             "quantize_gbs": (2 * 3 * 2 + 3) * BH * N * D / (times["quantize"] * 1e-3) / 1e9,
             "relative_difference_to_bf16_output": diff,
