@@ -163,3 +163,32 @@ def test_fp8_full_size_sampled_tiles():
         for a in tiles:
             r0, r1 = a * g.block_m, min(g.N, (a + 1) * g.block_m)
             assert_fp8_attn_close(torch.from_numpy(got[r0:r1]), ref[r0:r1], vmax, f"fp8 full size head {h} tile {a}")
+
+
+def test_fp8_batch_of_two_and_empty_list_rows():
+    """B = 2 (head index runs over batch and head), and a query tile whose list row is empty."""
+    cfg = dict(get_config("mid128"), B=2, H=3, spatial_heads=[0, 2])
+    cfg["N"] = cfg["F"] * cfg["P"] + cfg["T"]
+    sh, g = S.shape_from_config(cfg), O.Geometry.from_config(cfg)
+    q, k, v = make_plain_qkv(g.B, g.H, g.N, g.D, seed=77)
+    lab_np = planted_labels(cfg)
+    labels = torch.from_numpy(lab_np).cuda()
+    o = gpu_layer_fp8(sh, q.cuda(), k.cuda(), v.cuda(), labels)
+    ref = O.svg_attention_layer_fp8(f64(q), f64(k), f64(v), lab_np.reshape(g.B, g.H), g)
+    vmax = float(np.abs(f64(v)).max())
+    for b in range(g.B):
+        for h in range(g.H):
+            assert_fp8_attn_close(o[b, h], ref[b, h], vmax, f"fp8 batch b{b} h{h}")
+    # spatial list with the row of query tile 1 emptied, every head spatial
+    rp, ci = O.tile_list(g, 0)
+    rp2 = rp.copy()
+    rp2[2:] -= rp[2] - rp[1]
+    ci2 = np.concatenate([ci[:rp[1]], ci[rp[2]:]])
+    q8, k8, v8t, scales = gpu_fp8_quantize(sh, q.cuda(), k.cuda(), v.cuda(), None)
+    o2 = torch.full_like(o, 7.0)
+    S.svg_sparse_attn_fp8_fwd(sh, q8, k8, v8t, scales, o2, None, torch.from_numpy(rp2).cuda(),
+                              torch.from_numpy(ci2).cuda(), None, None)
+    torch.cuda.synchronize()
+    assert (o2[:, :, 128:256] == 0).all() and torch.isfinite(o2.float()).all()
+    full = gpu_layer_fp8(sh, q.cuda(), k.cuda(), v.cuda(), None)
+    assert torch.equal(o2[:, :, :128], full[:, :, :128]) and torch.equal(o2[:, :, 256:], full[:, :, 256:])
