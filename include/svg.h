@@ -6,7 +6,9 @@
  * transformation that makes the temporal pattern block-contiguous and its
  * inverse (Sec. 4.2, Fig. 4), a block-sparse FlashAttention-style forward pass
  * over the kept tiles (Sec. 4.3), and a dense forward pass as the in-library
- * baseline (the paper's baseline is dense FlashAttention, Sec. 5.3).
+ * baseline (the paper's baseline is dense FlashAttention, Sec. 5.3); further the
+ * fused QK-norm + rotary embedding pass in front of the attention (Sec. 4.3,
+ * Table 2) and the FP8 variant of the sparse pass (Sec. 4.3 "Quantization").
  *
  * Conventions for every entry point
  *   - Tensors q, k, v, o are DEVICE pointers to contiguous bf16 arrays of shape

@@ -60,7 +60,7 @@ const char* svg_strerror(int status) {
   }
 }
 
-const char* svg_version(void) { return "0.1"; }
+const char* svg_version(void) { return "0.2"; }
 
 const char* svg_last_hip_error(void) { return hipGetErrorString(svg::g_last_hip_error); }
 
