@@ -156,6 +156,7 @@ int launch_norm_rope(const Geo& g, const void* x, void* y, int norm, const float
   splits = splits > a.BH ? a.BH : splits;
   a.heads_per_block = (a.BH + splits - 1) / splits;
   const unsigned gy = (unsigned)((a.BH + a.heads_per_block - 1) / a.heads_per_block);
+  if (gy > 65535u) return SVG_ERR_UNSUPPORTED;
   (void)hipGetLastError();
   if (g.D == 128) hipLaunchKernelGGL(norm_rope_kernel<128>, dim3(gx, gy), dim3(256), 0, stream, a);
   else hipLaunchKernelGGL(norm_rope_kernel<64>, dim3(gx, gy), dim3(256), 0, stream, a);
