@@ -85,7 +85,7 @@ __global__ __launch_bounds__(256) void fp8_amax_kernel(const u32x4* q, const u32
   __shared__ unsigned red[256];
   red[threadIdx.x] = m;
   __syncthreads();
-  for (int step = 128; step > 0; step >>= 1) {
+  for (unsigned step = 128; step > 0; step >>= 1) {
     if (threadIdx.x < step) red[threadIdx.x] = max(red[threadIdx.x], red[threadIdx.x + step]);
     __syncthreads();
   }

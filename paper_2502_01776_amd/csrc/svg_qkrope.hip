@@ -81,9 +81,7 @@ __global__ __launch_bounds__(256) void norm_rope_kernel(NormRopeArgs a) {
 
   const size_t row = (size_t)n * CPR + c;
   const size_t head_stride = (size_t)a.N * CPR;
-#pragma unroll 4
-  for (int h = h0; h < h1; ++h) {
-    const u32x4 raw = __builtin_nontemporal_load(&a.in[h * head_stride + row]);
+  auto process = [&](const u32x4 raw, int h) {
     float x[8];
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
@@ -134,6 +132,17 @@ __global__ __launch_bounds__(256) void norm_rope_kernel(NormRopeArgs a) {
       o[2 * e + 1] = bits.y;
     }
     __builtin_nontemporal_store(o, &a.out[h * head_stride + row]);
+  };
+  // four heads at a time, their loads issued together
+  constexpr int kUnroll = 4;
+  for (int h = h0; h < h1; h += kUnroll) {
+    u32x4 raw[kUnroll];
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j)
+      if (h + j < h1) raw[j] = __builtin_nontemporal_load(&a.in[(h + j) * head_stride + row]);
+#pragma unroll
+    for (int j = 0; j < kUnroll; ++j)
+      if (h + j < h1) process(raw[j], h + j);
   }
 }
 
