@@ -867,7 +867,7 @@ __global__ __launch_bounds__(256) void profile_error_kernel(const float* ws, con
   red_s[threadIdx.x] = acc_s;
   red_t[threadIdx.x] = acc_t;
   __syncthreads();
-  for (int step = 128; step > 0; step >>= 1) {      // fixed order: deterministic
+  for (unsigned step = 128; step > 0; step >>= 1) {      // fixed order: deterministic
     if (threadIdx.x < step) {
       red_s[threadIdx.x] += red_s[threadIdx.x + step];
       red_t[threadIdx.x] += red_t[threadIdx.x + step];
