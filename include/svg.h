@@ -217,9 +217,11 @@ int svg_qk_norm_rope(const svg_shape_t* shape, const void* x, void* y, int norm,
  * FP8 attention (Sec. 4.3 "Quantization", Sec. 5.2: FP8 quantisation of the sparse
  * attention, applied at head dimension 128).  The paper names no format or scaling;
  * this library uses OCP E4M3 (largest finite value 448) with one scale per head and
- * tensor, scale = max|x| / 448 (1 for an all-zero head), x ~ code * scale, code = nearest
- * even of x * (1 / scale) with scale, reciprocal and product in float32.  Head dimension 128 and 128 x 64 tiles only, otherwise
- * SVG_ERR_UNSUPPORTED.
+ * tensor, scale = float32(max|x| / 448) (1 for an all-zero head), x ~ code * scale, code =
+ * the E4M3 value nearest to x / scale, ties to even.  The quotient is formed in float32 as
+ * x * (1 / scale): where the exact quotient lies within two float32 roundings (2^-23
+ * relative) of the midpoint of two E4M3 values, either neighbour may be returned.  Head
+ * dimension 128 and 128 x 64 tiles only, otherwise SVG_ERR_UNSUPPORTED.
  *
  * svg_fp8_quantize converts q, k, v (device bf16 [B,H,N,128], token order) into
  *   q8      uint8 [B,H,N,128], token order
@@ -232,7 +234,8 @@ int svg_qk_norm_rope(const svg_shape_t* shape, const void* x, void* y, int norm,
  *           scratch of the call
  * labels == NULL leaves every head in token order.  Buffer sizes in bytes:
  * svg_fp8_buffer_bytes(shape, SVG_FP8_Q / _K / _VT / _SCALES) (0 for an unsupported shape).
- * All buffers caller-owned, 16-byte aligned, distinct.
+ * All buffers caller-owned, 16-byte aligned, and distinct from each other and from q, k, v
+ * (SVG_ERR_ALIAS otherwise; likewise o of svg_sparse_attn_fp8_fwd against its inputs).
  *
  * svg_sparse_attn_fp8_fwd is svg_sparse_attn_fwd_ex(SVG_ATTN_QO_TOKEN_ORDER) on those
  * buffers: o (device bf16 [B,H,N,128]) is written in token order for every head, labels

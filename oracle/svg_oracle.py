@@ -119,20 +119,23 @@ def temporal_mask(g: Geometry, rows=None) -> np.ndarray:
 # ----------------------------------------------------------------------------
 # masked attention (Alg. 1 mask_attention)
 # ----------------------------------------------------------------------------
-def attention_weights(q: np.ndarray, k: np.ndarray, mask, scale: float) -> np.ndarray:
+def attention_weights(q: np.ndarray, k: np.ndarray, mask, scale: float, weight_round=None) -> np.ndarray:
     """Row-stochastic weights softmax(scale * q k^T) restricted to mask.  q [t,D],
-    k [N,D], mask bool [t,N] or None (= everything kept)."""
+    k [N,D], mask bool [t,N] or None (= everything kept).  weight_round (FP8 form only):
+    applied to the exponentials relative to the row maximum before they are normalised."""
     s = scale * (q @ k.T)
     if mask is not None:
         s = np.where(mask, s, -np.inf)
     s = s - s.max(axis=1, keepdims=True)
     e = np.exp(s)
+    if weight_round is not None:
+        e = weight_round(e)
     return e / e.sum(axis=1, keepdims=True)
 
 
-def masked_attention(q, k, v, mask, scale: float) -> np.ndarray:
+def masked_attention(q, k, v, mask, scale: float, weight_round=None) -> np.ndarray:
     """O = softmax_mask(scale * q k^T) v for one head.  q [t,D]; k, v [N,D]."""
-    return attention_weights(q, k, mask, scale) @ v
+    return attention_weights(q, k, mask, scale, weight_round) @ v
 
 
 # ----------------------------------------------------------------------------
@@ -218,7 +221,7 @@ def block_mask(g: Geometry, row_ptr, col_idx) -> np.ndarray:
 # ----------------------------------------------------------------------------
 # block-sparse attention (Sec. 4.3) and dense attention
 # ----------------------------------------------------------------------------
-def sparse_attention_head(q, k, v, row_ptr, col_idx, g: Geometry, q_tiles=None) -> np.ndarray:
+def sparse_attention_head(q, k, v, row_ptr, col_idx, g: Geometry, q_tiles=None, weight_round=None) -> np.ndarray:
     """One head, tensors [N,D] already in the order the tile list refers to.
     Each query tile attends to all in-range keys of its kept key tiles.
     q_tiles: optional iterable of query-tile indices; rows of other tiles are left
@@ -229,7 +232,7 @@ def sparse_attention_head(q, k, v, row_ptr, col_idx, g: Geometry, q_tiles=None) 
         r0, r1 = a * g.block_m, min(g.N, (a + 1) * g.block_m)
         kept = col_idx[row_ptr[a]:row_ptr[a + 1]]
         cols = np.concatenate([np.arange(b * g.block_n, min(g.N, (b + 1) * g.block_n)) for b in kept])
-        out[r0:r1] = masked_attention(q[r0:r1], k[cols], v[cols], None, g.scale)
+        out[r0:r1] = masked_attention(q[r0:r1], k[cols], v[cols], None, g.scale, weight_round)
     return out
 
 
@@ -262,7 +265,7 @@ def profile_heads(q, k, v, rows, g: Geometry):
     return mse, labels
 
 
-def svg_attention_layer(q, k, v, labels, g: Geometry):
+def svg_attention_layer(q, k, v, labels, g: Geometry, weight_round=None):
     """The sparse pass of one layer given the head labels: spatial heads run the
     block-sparse pass on the original order; temporal heads are permuted to the
     P-outer order, run the block-sparse pass with the temporal tile list, and the
@@ -274,10 +277,10 @@ def svg_attention_layer(q, k, v, labels, g: Geometry):
             lab = int(labels[b, h])
             rp, ci = lists[lab]
             if lab == SPATIAL:
-                out[b, h] = sparse_attention_head(q[b, h], k[b, h], v[b, h], rp, ci, g)
+                out[b, h] = sparse_attention_head(q[b, h], k[b, h], v[b, h], rp, ci, g, weight_round=weight_round)
             else:
                 o = sparse_attention_head(layout_fwd(q[b, h], g), layout_fwd(k[b, h], g),
-                                          layout_fwd(v[b, h], g), rp, ci, g)
+                                          layout_fwd(v[b, h], g), rp, ci, g, weight_round=weight_round)
                 out[b, h] = layout_inv(o, g)
     return out
 
@@ -289,11 +292,13 @@ def svg_attention_layer(q, k, v, labels, g: Geometry):
 # Reading (the paper only says that FP8 quantisation is applied to the sparse attention and
 # names no format or scaling): the OCP 8-bit format E4M3 (1 sign, 4 exponent bits with bias 7,
 # 3 mantissa bits, subnormals, largest finite value 448, no infinities) with one scale per
-# head and tensor, scale = max|x| / 448, code = nearest even of x * (1 / scale).  The decisions
-# that produce the integer codes (the scale, its reciprocal, the product, the rounding) are taken
-# in float32, the precision the kernel takes them in; everything after the codes is float64.  The oracle
-# defines the result as exact attention over the DEQUANTISED tensors; that the kernel also
-# rounds the attention weights to E4M3 before the second product is covered by the tolerance.
+# head and tensor.  The scale is an output of the quantiser (the attention pass multiplies by
+# it), so it is a float32 number: the float32 nearest to max|x| / 448.  The code of an element
+# is the E4M3 value nearest to the EXACT quotient x / scale, ties to the even mantissa; a
+# quotient beyond 448 (possible by one rounding of the scale) takes 448, the nearest value
+# the format has.  Everything after the codes is float64.  The result is defined as exact
+# attention over the DEQUANTISED tensors; an optional second form also represents the attention
+# weights in E4M3 (fp8_round_weights), the way a second product on 8-bit matrix units has to.
 # ----------------------------------------------------------------------------
 E4M3_MAX = 448.0
 
@@ -310,8 +315,8 @@ def e4m3_decode(codes) -> np.ndarray:
 
 
 def e4m3_encode(y) -> np.ndarray:
-    """Nearest E4M3 code of each value, ties to the even mantissa, magnitudes above 448
-    clamped to 448 (the kernel clamps before converting)."""
+    """Nearest E4M3 code of each value, ties to the even mantissa; magnitudes above 448 take
+    448 (the format has no larger value and no infinity)."""
     y = np.asarray(y, dtype=np.float64)
     a = np.minimum(np.abs(y), E4M3_MAX)
     code = np.zeros(a.shape, dtype=np.int64)
@@ -330,23 +335,36 @@ def e4m3_encode(y) -> np.ndarray:
 
 
 def fp8_quantize_head(x):
-    """x [N,D] (values exactly representable in float32) -> (codes uint8 [N,D], scale float32)
-    with x ~ decode(codes) * scale, scale = max|x| / 448 (1 if x is all zero)."""
-    x32 = np.asarray(x, dtype=np.float32)
-    amax = np.float32(np.max(np.abs(x32))) if x32.size else np.float32(0)
-    scale = np.float32(amax / np.float32(E4M3_MAX)) if amax > 0 else np.float32(1)
-    inv = np.float32(1) / scale
-    return e4m3_encode(x32 * inv), scale
+    """x [N,D] float64 -> (codes uint8 [N,D], scale float32) with x ~ decode(codes) * scale:
+    scale = float32(max|x| / 448) (1 if x is all zero), code = E4M3 value nearest to the exact
+    quotient x / scale (the float64 division of a 16-bit by a 24-bit significand is far below
+    any rounding boundary's resolution that matters here: boundaries are 5-bit numbers)."""
+    x = np.asarray(x, dtype=np.float64)
+    amax = float(np.max(np.abs(x))) if x.size else 0.0
+    scale = np.float32(amax / E4M3_MAX) if amax > 0 else np.float32(1)
+    return e4m3_encode(x / np.float64(scale)), scale
 
 
 def fp8_dequantize(codes, scale) -> np.ndarray:
     return e4m3_decode(codes) * np.float64(scale)
 
 
-def svg_attention_layer_fp8(q, k, v, labels, g: Geometry):
+FP8_WEIGHT_GAIN = 256.0   # weights are stored as 2^8 w, w in (0, 1]: non-zero down to 2^-18 of the row's largest
+
+
+def fp8_round_weights(e: np.ndarray) -> np.ndarray:
+    """Unnormalised attention weights e = exp(s - max s) in [0, 1] as an 8-bit second product
+    sees them: the E4M3 value nearest to 2^8 e (the power of two only moves the format's
+    range down so that small weights survive; it cancels when the row is normalised)."""
+    return e4m3_decode(e4m3_encode(FP8_WEIGHT_GAIN * e)) / FP8_WEIGHT_GAIN
+
+
+def svg_attention_layer_fp8(q, k, v, labels, g: Geometry, round_weights: bool = False):
     """The sparse pass of one layer with q, k, v of every head quantised to E4M3 first
     (per head and tensor); otherwise svg_attention_layer.  The quantisation is elementwise
-    with one scale per head, so it commutes with the layout transformation."""
+    with one scale per head, so it commutes with the layout transformation.  round_weights
+    additionally rounds every row's weights with fp8_round_weights before they are
+    normalised and applied to v."""
     dq = np.empty_like(q)
     dk = np.empty_like(k)
     dv = np.empty_like(v)
@@ -355,7 +373,7 @@ def svg_attention_layer_fp8(q, k, v, labels, g: Geometry):
             for src, dst in ((q, dq), (k, dk), (v, dv)):
                 codes, scale = fp8_quantize_head(src[b, h])
                 dst[b, h] = fp8_dequantize(codes, scale)
-    return svg_attention_layer(dq, dk, dv, labels, g)
+    return svg_attention_layer(dq, dk, dv, labels, g, weight_round=fp8_round_weights if round_weights else None)
 
 
 # ----------------------------------------------------------------------------

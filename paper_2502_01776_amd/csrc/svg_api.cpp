@@ -7,10 +7,11 @@ namespace {
 
 size_t tensor_bytes(const Geo& g) { return (size_t)g.B * g.H * g.N * g.D * 2; }
 
-bool overlap(const void* a, const void* b, size_t bytes) {
+bool overlap(const void* a, size_t a_bytes, const void* b, size_t b_bytes) {
   const uintptr_t x = reinterpret_cast<uintptr_t>(a), y = reinterpret_cast<uintptr_t>(b);
-  return x < y + bytes && y < x + bytes;
+  return x < y + b_bytes && y < x + a_bytes;
 }
+bool overlap(const void* a, const void* b, size_t bytes) { return overlap(a, bytes, b, bytes); }
 
 int check_qkvo(const void* q, const void* k, const void* v, const void* o) {
   if (!q || !k || !v || !o) return SVG_ERR_INVALID_ARG;
@@ -52,6 +53,7 @@ int svg_profile_heads(const svg_shape_t* shape, const void* q, const void* k, co
   if (!q || !k || !v || !rows || !labels || t <= 0) return SVG_ERR_INVALID_ARG;
   if (svg::misaligned16(q) || svg::misaligned16(k) || svg::misaligned16(v)) return SVG_ERR_INVALID_ARG;
   if ((int64_t)3 * g.B * g.H * ((t + g.bm - 1) / g.bm) > (int64_t)1 << 30) return SVG_ERR_UNSUPPORTED;
+  if ((int64_t)g.B * g.H > 65535) return SVG_ERR_UNSUPPORTED;      // heads are a grid dimension of the error pass
   if (!workspace || workspace_bytes < svg_workspace_bytes(shape, t)) return SVG_ERR_WORKSPACE;
   if (svg::misaligned16(workspace)) return SVG_ERR_INVALID_ARG;
   return svg::launch_profile(g, q, k, v, rows, t, labels, mse, static_cast<float*>(workspace),
@@ -146,6 +148,17 @@ int svg_fp8_quantize(const svg_shape_t* shape, const void* q, const void* k, con
   if (svg::misaligned16(q) || svg::misaligned16(k) || svg::misaligned16(v) || svg::misaligned16(q8) ||
       svg::misaligned16(k8) || svg::misaligned16(v8t) || svg::misaligned16(scales))
     return SVG_ERR_INVALID_ARG;
+  {
+    // the five outputs must be distinct from each other and from the three inputs
+    const size_t in_bytes = tensor_bytes(g);
+    const void* bufs[7] = {q8, k8, v8t, scales, q, k, v};
+    const size_t sizes[7] = {svg_fp8_buffer_bytes(shape, SVG_FP8_Q), svg_fp8_buffer_bytes(shape, SVG_FP8_K),
+                             svg_fp8_buffer_bytes(shape, SVG_FP8_VT), svg_fp8_buffer_bytes(shape, SVG_FP8_SCALES),
+                             in_bytes, in_bytes, in_bytes};
+    for (int i = 0; i < 4; ++i)
+      for (int j = i + 1; j < 7; ++j)
+        if (overlap(bufs[i], sizes[i], bufs[j], sizes[j])) return SVG_ERR_ALIAS;
+  }
   return svg::launch_fp8_quantize(g, q, k, v, labels, q8, k8, v8t, scales,
                                   static_cast<hipStream_t>(stream));
 }
@@ -163,6 +176,14 @@ int svg_sparse_attn_fp8_fwd(const svg_shape_t* shape, const void* q8, const void
   if (rc != SVG_OK) return rc;
   if (!row_ptr_s || !col_idx_s) return SVG_ERR_INVALID_ARG;
   if (labels && (!row_ptr_t || !col_idx_t)) return SVG_ERR_INVALID_ARG;
+  {
+    const size_t o_bytes = tensor_bytes(g);
+    if (overlap(o, o_bytes, q8, svg_fp8_buffer_bytes(shape, SVG_FP8_Q)) ||
+        overlap(o, o_bytes, k8, svg_fp8_buffer_bytes(shape, SVG_FP8_K)) ||
+        overlap(o, o_bytes, v8t, svg_fp8_buffer_bytes(shape, SVG_FP8_VT)) ||
+        overlap(o, o_bytes, scales, svg_fp8_buffer_bytes(shape, SVG_FP8_SCALES)))
+      return SVG_ERR_ALIAS;
+  }
   return svg::launch_fp8_attention(g, q8, k8, v8t, scales, o, labels, row_ptr_s, col_idx_s, row_ptr_t,
                                    col_idx_t, static_cast<hipStream_t>(stream));
 }

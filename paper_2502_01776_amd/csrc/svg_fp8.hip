@@ -393,7 +393,7 @@ __global__ __launch_bounds__(256, 2) void attn_fp8_kernel(Fp8Args a) {
       for (int kb = 0; kb < 2; ++kb)
 #pragma unroll
         for (int e = 0; e < 16; ++e)
-          if (col * kBN + 32 * kb + 8 * (e >> 2) + 4 * g + (e & 3) >= a.N) sacc[kb][e] = kNegBig;
+          if (col * kBN + 32 * kb + 8 * (e >> 2) + 4 * g + (e & 3) >= a.N) sacc[kb][e] = -INFINITY;
     }
     float tmax = sacc[0][0];
 #pragma unroll

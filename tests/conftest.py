@@ -10,9 +10,3 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X")
-
-
-def pytest_collection_modifyitems(config, items):
-    # GPU tests fail loudly (not skip) when selected on a box without a GPU;
-    # the CPU suite deselects them with -m "not gpu".
-    pass

@@ -124,7 +124,7 @@ def v8t_rows(v8t: np.ndarray, nk: int) -> np.ndarray:
     return rows.reshape(nk * 64, 128)
 
 
-FP8_REL_RMS = 0.05      # FP8 attention vs the oracle over the same quantised q, k, v
+FP8_REL_RMS = 0.03      # FP8 attention vs the oracle over the same quantised q, k, v (measured 1.2-2.1 %)
 
 
 def assert_fp8_attn_close(got: torch.Tensor, ref: np.ndarray, v_absmax: float, what=""):

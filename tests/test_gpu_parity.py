@@ -224,7 +224,7 @@ def test_profile_with_sink_and_unstructured_heads():
     rows = sample_rows(cfg, t=40)
     labels, mse = gpu_profile(sh, q.cuda(), k.cuda(), v.cuda(), rows)
     omse, olab = O.profile_heads(f64(q), f64(k), f64(v), rows, g)
-    assert labels_match(labels, omse, olab, rel=2e-2)
+    assert labels_match(labels, omse, olab)        # (measured: the two errors of these heads differ by 63-73 %)
     assert np.allclose(mse.cpu().numpy().reshape(omse.shape), omse, rtol=0.05, atol=2e-5)
 
 
@@ -362,6 +362,50 @@ def test_random_geometries_whole_layer():
         S.svg_dense_attn_fwd(sh, qc, kc, vc, od)
         torch.cuda.synchronize()
         assert_attn_close(od[0, 1], O.dense_attention_head(f64(q)[0, 1], f64(k)[0, 1], f64(v)[0, 1], g))
+
+
+def test_nothing_is_written_outside_the_outputs():
+    """Guard bytes in front of and behind o, labels, mse and the permuted tensors stay untouched
+    by profiling, the layout passes, both sparse pipelines and the dense pass (ragged last
+    query tile, ragged last key tile, head count that is no multiple of anything)."""
+    cfg, sh, g = setup("mid128", H=5, spatial_heads=[0, 3])
+    q, k, v = (x.cuda() for x in make_qkv(cfg))
+    BH, n = g.B * g.H, g.B * g.H * g.N * g.D
+    PAD = 4096          # bytes on each side; keeps the 16-byte alignment of the tensors
+
+    def guarded(nbytes, dtype):
+        buf = torch.full((PAD + nbytes + PAD,), 0xA5, dtype=torch.uint8, device="cuda")
+        return buf, buf[PAD:PAD + nbytes].view(dtype)
+
+    def intact(buf, nbytes):
+        return bool((buf[:PAD] == 0xA5).all()) and bool((buf[PAD + nbytes:] == 0xA5).all())
+
+    rows = sample_rows(cfg)
+    t = len(rows)
+    lab_buf, labels = guarded(BH, torch.uint8)
+    mse_buf, mse = guarded(BH * 2 * 4, torch.float32)
+    ws_bytes = S.svg_workspace_bytes(sh, t)
+    ws_buf, ws = guarded(ws_bytes, torch.uint8)
+    S.svg_profile_heads(sh, q, k, v, dev_i32(rows), t, labels, mse, ws, ws_bytes)
+    torch.cuda.synchronize()
+    assert intact(lab_buf, BH) and intact(mse_buf, BH * 8) and intact(ws_buf, ws_bytes)
+    assert np.array_equal(labels.cpu().numpy(), planted_labels(cfg))
+
+    bufs = {name: guarded(n * 2, torch.bfloat16) for name in ("qp", "kp", "vp", "op", "o", "o2", "od")}
+    view = {name: b[1].view(q.shape) for name, b in bufs.items()}
+    lists = device_tile_lists(sh)
+    S.svg_layout_fwd(sh, q, view["qp"], labels)
+    S.svg_layout_fwd(sh, k, view["kp"], labels)
+    S.svg_layout_fwd(sh, v, view["vp"], labels)
+    S.svg_sparse_attn_fwd(sh, view["qp"], view["kp"], view["vp"], view["op"], labels, *lists)
+    S.svg_layout_inv(sh, view["op"], view["o"], labels)
+    S.svg_sparse_attn_fwd_ex(sh, q, view["kp"], view["vp"], view["o2"], labels, *lists,
+                             flags=S.SVG_ATTN_QO_TOKEN_ORDER | S.SVG_ATTN_ELEMENT_MASK)
+    S.svg_dense_attn_fwd(sh, q, k, v, view["od"])
+    torch.cuda.synchronize()
+    for name, (buf, _) in bufs.items():
+        assert intact(buf, n * 2), name
+    assert torch.isfinite(view["o"].float()).all() and torch.isfinite(view["od"].float()).all()
 
 
 def test_large_logits_do_not_overflow():
