@@ -788,8 +788,11 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
 
 // Groups the sampled rows by in-frame position for the temporal profiling variant:
 // order[] receives the indices 0..t-1 sorted by a coarse position bin (text rows
-// first).  One workgroup, counting sort with LDS atomics; the order inside a bin is
-// arbitrary, which is harmless because every result is written back to its own slot.
+// first), ascending inside a bin.  One workgroup, counting sort with LDS atomics; the
+// atomics leave the order inside a bin to chance, and which rows share a wavefront
+// decides where that wavefront renews its reference maximum, i.e. the rounding of the
+// results, so every bin is sorted afterwards to make the grouping, and with it every
+// output bit, the same on every run.
 constexpr int kOrderBins = 2048;
 __global__ __launch_bounds__(1024) void profile_order_kernel(const int32_t* rows, int t, int off,
                                                              int video_end, int P, int32_t* order) {
@@ -820,6 +823,20 @@ __global__ __launch_bounds__(1024) void profile_order_kernel(const int32_t* rows
   hist[2 * tid + 1] = base + h0;
   __syncthreads();
   for (int i = tid; i < t; i += 1024) order[atomicAdd(&hist[bin_of(rows[i])], 1)] = i;
+  __syncthreads();
+  // hist[b] is now the end of bin b; insertion sort of each (short) bin by row index
+  for (int b = 2 * tid; b < 2 * tid + 2; ++b) {
+    const int s = b == 0 ? 0 : hist[b - 1], e = hist[b];
+    for (int i = s + 1; i < e; ++i) {
+      const int x = order[i];
+      int j = i - 1;
+      while (j >= s && order[j] > x) {
+        order[j + 1] = order[j];
+        --j;
+      }
+      order[j + 1] = x;
+    }
+  }
 }
 
 // Squared errors of the two masked outputs against the unmasked one (Alg. 1, last

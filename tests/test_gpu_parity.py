@@ -293,6 +293,14 @@ def test_results_are_deterministic():
     o1 = gpu_layer(sh, q, k, v, l1)
     o2 = gpu_layer(sh, q, k, v, l1)
     assert torch.equal(o1.view(torch.int16), o2.view(torch.int16))
+    # many sampled rows at the same in-frame position (they share a bin of the row grouping of
+    # the temporal pass), with unrelated work in between so that the timing differs
+    rows = sample_rows(cfg, t=600)
+    l1, m1 = gpu_profile(sh, q, k, v, rows)
+    for _ in range(3):
+        gpu_layer(sh, q, k, v, l1)
+        l2, m2 = gpu_profile(sh, q, k, v, rows)
+        assert torch.equal(l1, l2) and torch.equal(m1, m2)
 
 
 # ------------------------------------------------------------------ degenerate geometries
