@@ -121,6 +121,23 @@ int svg_profile_heads(const svg_shape_t* shape, const void* q, const void* k, co
                       void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * svg_profile_heads for callers that cannot allocate device memory or hand over a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc.  Same computation, same kernels, same results bit for bit; the workspace is an
+ * array of SVG_STATIC_SCRATCH_BYTES that is part of the library's code object (each GPU the
+ * library runs on holds one copy until the process ends).  The call allocates and frees
+ * nothing.  A shape and t with svg_workspace_bytes(shape, t) > SVG_STATIC_SCRATCH_BYTES is
+ * refused with SVG_ERR_WORKSPACE before anything is enqueued (160 MiB covers every benchmark
+ * shape at 1 % sampled rows, the 119k-token one needs 148 MB).  All calls on one GPU share
+ * that GPU's array: calls that overlap in time on one GPU (other streams, other threads)
+ * race; calls ordered on one stream do not.  Nothing in the array has to be cleared between
+ * calls.
+ */
+#define SVG_STATIC_SCRATCH_BYTES (160u << 20)
+int svg_profile_heads_static(const svg_shape_t* shape, const void* q, const void* k, const void* v,
+                             const int32_t* rows, int32_t t, uint8_t* labels, float* mse, void* stream);
+
+/*
  * Layout transformation (Sec. 4.2, Fig. 4): for heads labelled temporal,
  * out[b,h, off + p*F + f, :] = in[b,h, off + f*P + p, :]; text rows and heads
  * labelled spatial are copied unchanged, so `out` is always fully written.

@@ -26,7 +26,7 @@ SVG_ATTN_ELEMENT_MASK = 2            # svg_sparse_attn_fwd_ex: the pattern's ele
 SVG_OK = 0
 
 EXPORTS = ("svg_strerror", "svg_version", "svg_last_hip_error", "svg_workspace_bytes", "svg_tile_counts",
-           "svg_tile_list_build", "svg_profile_heads", "svg_layout_fwd", "svg_layout_inv",
+           "svg_tile_list_build", "svg_profile_heads", "svg_profile_heads_static", "svg_layout_fwd", "svg_layout_inv",
            "svg_sparse_attn_fwd", "svg_sparse_attn_fwd_ex", "svg_dense_attn_fwd",
            "svg_fp8_buffer_bytes", "svg_fp8_quantize", "svg_sparse_attn_fp8_fwd", "svg_qk_norm_rope")
 
@@ -77,6 +77,8 @@ def lib():
         L.svg_tile_list_build.argtypes = [sp, C.c_int, vp, vp, C.c_int64, C.POINTER(C.c_int64)]
         L.svg_profile_heads.restype = C.c_int
         L.svg_profile_heads.argtypes = [sp, vp, vp, vp, vp, C.c_int32, vp, vp, vp, C.c_size_t, vp]
+        L.svg_profile_heads_static.restype = C.c_int
+        L.svg_profile_heads_static.argtypes = [sp, vp, vp, vp, vp, C.c_int32, vp, vp, vp]
         for name in ("svg_layout_fwd", "svg_layout_inv"):
             f = getattr(L, name)
             f.restype = C.c_int
@@ -167,6 +169,14 @@ def svg_profile_heads(shape, q, k, v, rows, t, labels, mse, workspace, workspace
     _check(lib().svg_profile_heads(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(rows), int(t),
                                    _ptr(labels), _ptr(mse), _ptr(workspace), int(workspace_bytes),
                                    _stream(stream)), "svg_profile_heads")
+
+
+SVG_STATIC_SCRATCH_BYTES = 160 << 20
+
+
+def svg_profile_heads_static(shape, q, k, v, rows, t, labels, mse, stream=None):
+    _check(lib().svg_profile_heads_static(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(rows), int(t),
+                                          _ptr(labels), _ptr(mse), _stream(stream)), "svg_profile_heads_static")
 
 
 def svg_layout_fwd(shape, x, out, labels=None, stream=None):

@@ -50,10 +50,8 @@ int svg_profile_heads(const svg_shape_t* shape, const void* q, const void* k, co
   Geo g;
   int rc = svg::make_geo(shape, &g);
   if (rc != SVG_OK) return rc;
-  if (!q || !k || !v || !rows || !labels || t <= 0) return SVG_ERR_INVALID_ARG;
-  if (svg::misaligned16(q) || svg::misaligned16(k) || svg::misaligned16(v)) return SVG_ERR_INVALID_ARG;
-  if ((int64_t)3 * g.B * g.H * ((t + g.bm - 1) / g.bm) > (int64_t)1 << 30) return SVG_ERR_UNSUPPORTED;
-  if ((int64_t)g.B * g.H > 65535) return SVG_ERR_UNSUPPORTED;      // heads are a grid dimension of the error pass
+  rc = svg::check_profile_args(g, q, k, v, rows, t, labels);
+  if (rc != SVG_OK) return rc;
   if (!workspace || workspace_bytes < svg_workspace_bytes(shape, t)) return SVG_ERR_WORKSPACE;
   if (svg::misaligned16(workspace)) return SVG_ERR_INVALID_ARG;
   return svg::launch_profile(g, q, k, v, rows, t, labels, mse, static_cast<float*>(workspace),

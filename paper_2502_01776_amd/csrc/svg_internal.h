@@ -36,6 +36,16 @@ inline size_t profile_workspace_bytes(const Geo& g, int t) {
 
 inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
+// Argument checks shared by the profiling entry points (everything except the workspace).
+inline int check_profile_args(const Geo& g, const void* q, const void* k, const void* v, const int32_t* rows,
+                              int32_t t, const uint8_t* labels) {
+  if (!q || !k || !v || !rows || !labels || t <= 0) return SVG_ERR_INVALID_ARG;
+  if (misaligned16(q) || misaligned16(k) || misaligned16(v)) return SVG_ERR_INVALID_ARG;
+  if ((int64_t)3 * g.B * g.H * ((t + g.bm - 1) / g.bm) > (int64_t)1 << 30) return SVG_ERR_UNSUPPORTED;
+  if ((int64_t)g.B * g.H > 65535) return SVG_ERR_UNSUPPORTED;      // heads are a grid dimension of the error pass
+  return SVG_OK;
+}
+
 // Remembers the most recent HIP error of the calling thread for svg_last_hip_error().
 void note_hip_error(hipError_t e);
 inline int hip_status(hipError_t e) {
