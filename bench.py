@@ -3,11 +3,13 @@
 
 A step is one pass of the whole hot path over one synthetic layer input that is
 already resident in HBM: online profiling (three masked attentions over the
-sampled rows + MSE + label), layout transform of k and v, block-sparse attention
+sampled rows + MSE + label), layout transform of k and v of the heads labelled
+temporal (one launch; spatial heads are read in place), block-sparse attention
 over the kept tiles with the layout transform of q and the inverse transform of o
 folded into the kernel (--four-layout-passes: as four separate passes over q, k, v
-and o).  The in-library dense attention is timed beside it, and the CPU oracle is
-timed on a bounded sample.
+and o of all heads).  The in-library dense attention is timed beside it, the
+matrix cores' sustained rate is measured by a product-only loop, and the CPU oracle
+is timed on a bounded sample (in full for the two small workloads).
 
 Prints ONE JSON line on stdout.
 """
@@ -51,6 +53,8 @@ def parse():
     ap.add_argument("--no-qk-norm-rope", action="store_true",
                     help="skip the timing of the fused QK-norm + rotary embedding pass on q and k (Table 2), "
                          "otherwise reported in the 'qk_norm_rope' object beside a plain PyTorch version")
+    ap.add_argument("--no-measured-peak", action="store_true",
+                    help="skip the two product loops that measure what the matrix cores sustain on this box")
     ap.add_argument("--only", default="", help="time a single stage only (profile|layout|sparse|dense); "
                     "used for per-kernel rocprofv3 runs")
     return ap.parse_args()
@@ -61,17 +65,48 @@ def ev():
     return torch.cuda.Event(enable_timing=True)
 
 
-def cpu_baseline(cfg, q, k, v, rows, labels_np, nnz_total):
-    """Oracle timed on a bounded sample of the same workload: profiling of one head on
-    a subset of the sampled rows, and the block-sparse pass of a few query tiles of
-    one spatial and one temporal head.  Extrapolated linearly to one layer."""
+def blas_threads():
+    """Threads of the BLAS pool numpy's matrix products run on (the oracle's only parallel part)."""
+    try:
+        from threadpoolctl import threadpool_info
+        n = [i.get("num_threads", 1) for i in threadpool_info() if i.get("user_api") == "blas"]
+        return max(n) if n else 1
+    except Exception:
+        return 1
+
+
+def rel_rms(a, b):
+    import numpy as np
+    return float(np.linalg.norm(a - b) / max(np.linalg.norm(b), 1e-30))
+
+
+def cpu_baseline(cfg, q, k, v, rows, labels_np, nnz_total, o_bf16=None, o_fp8=None):
+    """The oracle as it stands, timed on the host cores of this machine.  The two small workloads
+    are timed in full; for the others a bounded sample of independent units is timed
+    (profiling of one head of each label on a subset of the sampled rows, the block-sparse pass
+    of a few query tiles of one spatial and one temporal head) and scaled linearly to a layer."""
     import numpy as np
     import torch
     from oracle import svg_oracle as O
     g = O.Geometry.from_config(cfg)
     nq, nk = O.n_tiles(g)
-    threads = torch.get_num_threads()
+    host_cpus = len(os.sched_getaffinity(0))
     f64 = lambda x: x.cpu().to(torch.float64).numpy()
+    dense_flops = 4.0 * g.N * g.N * g.D * g.H * g.B
+    if cfg["name"] in ("tiny", "cogvideox_v1"):
+        qd, kd, vd = f64(q), f64(k), f64(v)
+        t0 = time.perf_counter()
+        _, olab = O.profile_heads(qd, kd, vd, rows, g)
+        t_prof = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        O.svg_attention_layer(qd, kd, vd, olab, g)
+        t_attn = time.perf_counter() - t0
+        layer_s = t_prof + t_attn
+        return {"value": dense_flops / layer_s / 1e12, "unit": "TFLOP/s (effective)", "cores": blas_threads(),
+                "host_cpus": host_cpus, "kind": "oracle", "extrapolated": False, "ms_per_layer": layer_s * 1e3,
+                "sample": (f"fp64 numpy oracle, the whole layer: profiling of all {g.B * g.H} heads on all "
+                           f"{len(rows)} sampled rows ({t_prof:.1f} s) + tile lists, layout and block-sparse pass "
+                           f"of all heads ({t_attn:.1f} s)")}
     h_s = int(np.argmax(labels_np == 0)) if (labels_np == 0).any() else 0
     h_t = int(np.argmax(labels_np == 1)) if (labels_np == 1).any() else 0
     budget_rows = max(8, min(len(rows), int(2.0e8 // g.N)))      # bounds the t x N score matrices
@@ -88,6 +123,7 @@ def cpu_baseline(cfg, q, k, v, rows, labels_np, nnz_total):
 
     tiles_done, t_attn = 0, 0.0
     n_sample = 64
+    fp8_split = None
     for pat, h in ((O.SPATIAL, h_s), (O.TEMPORAL, h_t)):
         qh, kh, vh = f64(q[0, h]), f64(k[0, h]), f64(v[0, h])
         pick = sorted(set(int(x) for x in np.linspace(0, nq - 1, n_sample + 2)[1:-1]))
@@ -101,19 +137,76 @@ def cpu_baseline(cfg, q, k, v, rows, labels_np, nnz_total):
             cols.append(c)
             rp[a + 1] = rp[a] + len(c)
             tiles_done += len(c)
-        O.sparse_attention_head(qh, kh, vh, rp, np.concatenate(cols), g, q_tiles=pick)
+        ref16 = O.sparse_attention_head(qh, kh, vh, rp, np.concatenate(cols), g, q_tiles=pick)
         t_attn += time.perf_counter() - t0
+        if o_fp8 is not None and o_bf16 is not None:
+            # Where the FP8 layer's difference to the bf16 layer comes from (not timed): the
+            # quantisation of q, k, v (oracle over the dequantised tensors against the oracle over
+            # the originals), the 8-bit attention weights (oracle with rounded weights against the
+            # one without), and the kernel against each; on a few of the sampled query tiles.
+            few = pick[:: max(1, len(pick) // 6)]
+            dq, dk, dv = (O.fp8_dequantize(*O.fp8_quantize_head(x)) for x in (qh, kh, vh))   # elementwise: any order
+            keep = np.concatenate([np.arange(a * g.block_m, min(g.N, (a + 1) * g.block_m)) for a in few])
+            rp2 = np.zeros(nq + 1, dtype=np.int64)
+            cols2 = []
+            for a in range(nq):
+                c = cols[a] if a in few else np.zeros(0, np.int32)
+                cols2.append(c)
+                rp2[a + 1] = rp2[a] + len(c)
+            ci2 = np.concatenate(cols2)
+            ref8 = O.sparse_attention_head(dq, dk, dv, rp2, ci2, g, q_tiles=few)[keep]
+            ref8r = O.sparse_attention_head(dq, dk, dv, rp2, ci2, g, q_tiles=few, weight_round=O.fp8_round_weights)[keep]
+            got8, got16 = f64(o_fp8[0, h]), f64(o_bf16[0, h])
+            if pat == O.TEMPORAL:
+                got8, got16 = O.layout_fwd(got8, g), O.layout_fwd(got16, g)
+            part = {"input_quantisation (oracle fp8 vs oracle bf16)": rel_rms(ref8, ref16[keep]),
+                    "weight_rounding (oracle 8-bit weights vs oracle fp8)": rel_rms(ref8r, ref8),
+                    "kernel_fp8_vs_oracle_fp8": rel_rms(got8[keep], ref8),
+                    "kernel_fp8_vs_oracle_fp8_with_8bit_weights": rel_rms(got8[keep], ref8r),
+                    "kernel_bf16_vs_oracle_bf16": rel_rms(got16[keep], ref16[keep]),
+                    "kernel_fp8_vs_kernel_bf16": rel_rms(got8[keep], got16[keep])}
+            fp8_split = fp8_split or {"relative_rms_on": f"{len(few)} query tiles of one head per label"}
+            fp8_split["spatial_head" if pat == O.SPATIAL else "temporal_head"] = part
     attn_layer_s = t_attn / max(tiles_done, 1) * nnz_total
     layer_s = prof_layer_s + attn_layer_s
-    dense_flops = 4.0 * g.N * g.N * g.D * g.H * g.B
-    return {
-        "value": dense_flops / layer_s / 1e12, "unit": "TFLOP/s (effective)", "cores": threads,
-        "kind": "oracle", "extrapolated": True, "ms_per_layer": layer_s * 1e3,
+    out = {
+        "value": dense_flops / layer_s / 1e12, "unit": "TFLOP/s (effective)", "cores": blas_threads(),
+        "host_cpus": host_cpus, "kind": "oracle", "extrapolated": True, "ms_per_layer": layer_s * 1e3,
         "sample": (f"fp64 numpy oracle: profiling of {n_prof_heads} heads on {len(sub)} of {len(rows)} sampled rows "
                    f"({t_prof:.1f} s) + block-sparse pass of {n_sample} query tiles of one spatial and "
                    f"one temporal head incl. tile-list rows and layout ({t_attn:.1f} s, {tiles_done} "
                    f"tiles); scaled linearly to {g.B * g.H} heads, {len(rows)} rows, {nnz_total} tiles"),
     }
+    if fp8_split:
+        out["fp8_error_split"] = fp8_split
+    return out
+
+
+def measured_matrix_peak(S, torch, ms_target=12.0):
+    """Sustained rate of the bf16 matrix cores on this machine: a loop of products only (form 0) and
+    the same loop with the per-product LDS read and softmax instructions of the D = 128 attention
+    kernel (form 1), on normally distributed operands, each timed over >= 10 ms."""
+    gen = torch.Generator(device="cuda").manual_seed(11)
+    operands = torch.randn(1 << 19, generator=gen, device="cuda").to(torch.bfloat16)      # 1 MiB
+    wgs = 2048
+    sink = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
+    out = {}
+    for form, key in ((0, "products_only"), (1, "with_lds_operand_reads_and_softmax_instructions")):
+        iters = 500
+        for attempt in range(3):
+            S.svg_probe_mfma_bf16(form, wgs, iters, operands, sink)          # warm-up / calibration
+            torch.cuda.synchronize()
+            e0, e1 = ev(), ev()
+            e0.record()
+            flop = S.svg_probe_mfma_bf16(form, wgs, iters, operands, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1)
+            if ms >= ms_target * 0.8:
+                break
+            iters = int(iters * ms_target / max(ms, 1e-3)) + 1
+        out[key] = {"tflops": flop / (ms * 1e-3) / 1e12, "ms": ms}
+    return out
 
 
 def main():
@@ -158,14 +251,16 @@ def main():
     folded = not args.four_layout_passes
 
     def stage_layout_fwd():
-        if not folded:
+        if folded:
+            S.svg_layout_kv_temporal(sh, k, v, kp, vp, labels)
+        else:
             S.svg_layout_fwd(sh, q, qp, labels)
-        S.svg_layout_fwd(sh, k, kp, labels)
-        S.svg_layout_fwd(sh, v, vp, labels)
+            S.svg_layout_fwd(sh, k, kp, labels)
+            S.svg_layout_fwd(sh, v, vp, labels)
 
     def stage_sparse():
         if folded:
-            S.svg_sparse_attn_fwd_ex(sh, q, kp, vp, o, labels, *lists, flags=S.SVG_ATTN_QO_TOKEN_ORDER)
+            S.svg_sparse_attn_fwd_kv2(sh, q, k, v, kp, vp, o, labels, *lists)
         else:
             S.svg_sparse_attn_fwd(sh, qp, kp, vp, op, labels, *lists)
 
@@ -215,7 +310,7 @@ def main():
         step(marks)
     torch.cuda.synchronize()
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
-    breakdown = {name: float(np.mean([a.elapsed_time(b) for a, b in lst])) for name, lst in marks.items()}
+    breakdown = {name: float(np.median([a.elapsed_time(b) for a, b in lst])) for name, lst in marks.items()}
 
     labels_np = labels.cpu().numpy()
     n_temporal = int(labels_np.sum())
@@ -228,13 +323,15 @@ def main():
         od = op        # reuse a buffer
         S.svg_dense_attn_fwd(sh, q, k, v, od)
         torch.cuda.synchronize()
-        e0, e1 = ev(), ev()
-        e0.record()
+        dense_times = []
         for _ in range(args.dense_reps):
+            e0, e1 = ev(), ev()
+            e0.record()
             S.svg_dense_attn_fwd(sh, q, k, v, od)
-        e1.record()
-        torch.cuda.synchronize()
-        dense_ms = e0.elapsed_time(e1) / args.dense_reps
+            e1.record()
+            torch.cuda.synchronize()
+            dense_times.append(e0.elapsed_time(e1))
+        dense_ms = float(np.median(dense_times))
 
     dense_flops = 4.0 * N * N * D * BH
     tile_flops = 4.0 * cfg["block_m"] * cfg["block_n"] * D
@@ -251,9 +348,13 @@ def main():
             prof = json.load(f)
         traffic = prof.get("sparse_attn_bytes_per_launch")
         if "sparse_attn_mfma_busy_fraction_of_cycles" in prof:
-            counters = {"mfma_busy_fraction_of_cycles": prof["sparse_attn_mfma_busy_fraction_of_cycles"],
+            counters = {"live": False, "measured_on": prof.get("measured_on", "another box of the pool, see source"),
+                        "mfma_busy_fraction_of_cycles": prof["sparse_attn_mfma_busy_fraction_of_cycles"],
                         "shader_clock_ghz": prof["sparse_attn_shader_clock_ghz"], "source": prof.get("source")}
-    layout_bytes = 2.0 * n_temporal * N * D * 2 + 2.0 * (BH - n_temporal) * N * D * 2   # read + write, all heads
+    # algorithmic bytes of the layout stage: one read and one write of every tensor row that has to move
+    # (temporal heads only); the four-pass form also copies the spatial heads, which is not counted
+    layout_bytes = 2.0 * n_temporal * N * D * 2
+    peak_live = None if args.no_measured_peak else measured_matrix_peak(S, torch)
     out = {
         "metric": "effective TFLOP/s of one sparse attention layer at %dk tokens "
                   "(4*N^2*D*H / ms per layer; profile + layout + block-sparse attention + inverse layout%s)"
@@ -271,8 +372,10 @@ def main():
         "dense_ms": dense_ms,
         "dense_tflops": None if dense_ms is None else dense_flops / (dense_ms * 1e-3) / 1e12,
         "speedup_vs_dense": None if dense_ms is None else dense_ms / wall_ms,
-        "layout_passes": "k v (q and o inside the attention kernel)" if folded else "q k v o",
+        "layout_passes": "k and v of temporal heads in one launch (q and o inside the attention kernel, spatial heads "
+                         "read in place)" if folded else "q k v o, all heads",
         "layout_gbs": {"fwd": (2 if folded else 3) * layout_bytes / (breakdown["layout_fwd"] * 1e-3) / 1e9,
+                       "counts": "rows of temporal heads only, read + write",
                        "inv_o": None if folded else layout_bytes / (breakdown["layout_inv"] * 1e-3) / 1e9},
         # the three masked passes of Alg. 1 counted in full (3 x 4 t N D per head), although the
         # kernel skips the key tiles no sampled row of a workgroup keeps
@@ -282,8 +385,19 @@ def main():
         "profile_kv_gbs": 2.0 * BH * N * D * 2 / (breakdown["profile"] * 1e-3) / 1e9,
         "roofline": {"kernel": "attn_kernel<128,4,64,sparse>" if D == 128 else "attn_kernel<64,4,128,sparse>",
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic, "counters": counters},
+                     "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
+                     "traffic_live": False if traffic is not None else None, "counters": counters},
     }
+    if peak_live:
+        # what the matrix cores sustain on THIS box at the clock a matrix load runs at (live, HIP events)
+        mp = peak_live["products_only"]["tflops"]
+        mix = peak_live["with_lds_operand_reads_and_softmax_instructions"]["tflops"]
+        out["roofline"]["measured_peak"] = mp
+        out["roofline"]["frac_of_measured_peak"] = achieved / mp
+        out["roofline"]["measured_peak_with_kernel_instruction_mix"] = mix
+        out["roofline"]["frac_of_instruction_mix_bound"] = achieved / mix
+        out["roofline"]["measured_peak_detail"] = peak_live
+    o8_keep = None
     if not args.no_fp8 and S.svg_fp8_buffer_bytes(sh, S.SVG_FP8_Q) > 0:
         # the same layer with the sparse pass in FP8: profiling as above (bf16), one quantisation pass
         # (per-head maxima, conversion, layout of k and v of temporal heads), FP8 attention
@@ -313,6 +427,7 @@ def main():
             diff = (o8.float() - o.float()).norm().item() / max(o.float().norm().item(), 1e-30)
         else:
             diff = None
+        o8_keep = o8
         layer8 = breakdown["profile"] + times["quantize"] + times["sparse_attn"]
         tf8 = tile_flops * nnz_total / (times["sparse_attn"] * 1e-3) / 1e12
         out["fp8"] = {
@@ -327,7 +442,9 @@ def main():
             "roofline": {"kernel": "attn_fp8_kernel", "bound": "mfma", "achieved": tf8, "peak": PEAK_FP8_TFLOPS,
                          "unit": "TFLOP/s", "frac": tf8 / PEAK_FP8_TFLOPS,
                          "traffic": prof.get("fp8_attn_bytes_per_launch"),
+                         "traffic_live": False if prof.get("fp8_attn_bytes_per_launch") is not None else None,
                          "counters": None if "fp8_attn_mfma_busy_fraction_of_cycles" not in prof else {
+                             "live": False,
                              "mfma_busy_fraction_of_cycles": prof["fp8_attn_mfma_busy_fraction_of_cycles"],
                              "shader_clock_ghz": prof["fp8_attn_shader_clock_ghz"], "source": prof.get("source")}},
             # bytes of the quantisation pass: q, k, v read twice (maxima, conversion), written once as bytes
@@ -411,7 +528,8 @@ def main():
             "with_transform_ms_per_layer": wall_ms,
             "speedup_from_transform": (breakdown["profile"] + ms2) / wall_ms}
     if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, rows_np, labels_np, nnz_total)
+        out["cpu_baseline"] = cpu_baseline(cfg, q, k, v, rows_np, labels_np, nnz_total,
+                                           o_bf16=o if folded else None, o_fp8=o8_keep)
     print(json.dumps(out))
 
 

@@ -199,6 +199,28 @@ int svg_sparse_attn_fwd_ex(const svg_shape_t* shape, const void* q, const void* 
                            size_t workspace_bytes, void* stream);
 
 /*
+ * The sparse pass of one layer with as little layout traffic as the method needs (Sec. 4.2,
+ * Sec. 4.3: the transformation is fused into the kernels).  Only k and v of the heads
+ * labelled temporal are moved at all:
+ *   svg_layout_kv_temporal   one launch: for every head labelled temporal,
+ *       k_t[b,h, off + p*F + f, :] = k[b,h, off + f*P + p, :] and likewise v_t from v (text
+ *       rows copied); the slots of heads labelled spatial in k_t, v_t are NOT written (and
+ *       never read by the call below).  k_t, v_t: device bf16 [B,H,N,D], distinct from k, v
+ *       and from each other (SVG_ERR_ALIAS).  labels must not be NULL.
+ *   svg_sparse_attn_fwd_kv2  block-sparse attention in which a head labelled spatial reads k, v
+ *       (original order) and a head labelled temporal reads k_t, v_t; q is read and o written
+ *       in the original token order for every head (as with SVG_ATTN_QO_TOKEN_ORDER).  Results
+ *       are bit-identical to svg_layout_fwd(q, k, v) -> svg_sparse_attn_fwd -> svg_layout_inv(o).
+ *       flags: 0 or SVG_ATTN_ELEMENT_MASK.  labels and both tile lists are required.
+ */
+int svg_layout_kv_temporal(const svg_shape_t* shape, const void* k, const void* v, void* k_t, void* v_t,
+                           const uint8_t* labels, void* stream);
+int svg_sparse_attn_fwd_kv2(const svg_shape_t* shape, const void* q, const void* k, const void* v,
+                            const void* k_t, const void* v_t, void* o, const uint8_t* labels,
+                            const int32_t* row_ptr_s, const int32_t* col_idx_s, const int32_t* row_ptr_t,
+                            const int32_t* col_idx_t, uint32_t flags, void* stream);
+
+/*
  * Dense attention forward, o = softmax(scale * q k^T) v per head: the baseline
  * the paper measures against (Sec. 5.3) and the pass used on the dense warm-up
  * steps (Sec. 5.1).  Same tensors and precision as svg_sparse_attn_fwd; every
@@ -270,6 +292,27 @@ int svg_sparse_attn_fp8_fwd(const svg_shape_t* shape, const void* q8, const void
                             const void* v8t, const float* scales, void* o, const uint8_t* labels,
                             const int32_t* row_ptr_s, const int32_t* col_idx_s,
                             const int32_t* row_ptr_t, const int32_t* col_idx_t, void* stream);
+
+/*
+ * Measurement aid, not a step of the method: the rate the bf16 matrix cores sustain on this
+ * GPU, which the roofline of the attention kernels (Sec. 5.3: kernel-level efficiency) is
+ * read against besides the published peak.  Launches `workgroups` workgroups of 4
+ * wavefronts (two resident per compute unit), each wavefront issuing 16 * iterations
+ * products v_mfma_f32_32x32x16_bf16 on operands taken from `operands`.
+ *   form 0   products only, operands in registers
+ *   form 1   per product additionally one 1 KB operand read from LDS and the softmax
+ *            instructions the D = 128 attention kernel spends per product (one FMA, one
+ *            exponential, one addition, half a bf16 pack): an upper bound for that kernel
+ *            design, without its staging, barriers and global memory traffic
+ *   operands device, 1 MiB, 16-byte aligned: bf16 values (random data draws the power real
+ *            data draws; zeros would let the clock rise)
+ *   sink     device float [workgroups * 256], written (keeps the products alive)
+ *   flop_out host, may be NULL: receives the floating point operations of the launch
+ *            (2 * 32 * 32 * 16 per product)
+ * The caller times the launch (it should last >= 10 ms for the clock to settle).
+ */
+int svg_probe_mfma_bf16(int form, int32_t workgroups, int32_t iterations, const void* operands,
+                        float* sink, double* flop_out, void* stream);
 
 #ifdef __cplusplus
 }

@@ -28,7 +28,9 @@ SVG_OK = 0
 EXPORTS = ("svg_strerror", "svg_version", "svg_last_hip_error", "svg_workspace_bytes", "svg_tile_counts",
            "svg_tile_list_build", "svg_profile_heads", "svg_profile_heads_static", "svg_layout_fwd", "svg_layout_inv",
            "svg_sparse_attn_fwd", "svg_sparse_attn_fwd_ex", "svg_dense_attn_fwd",
-           "svg_fp8_buffer_bytes", "svg_fp8_quantize", "svg_sparse_attn_fp8_fwd", "svg_qk_norm_rope")
+           "svg_layout_kv_temporal", "svg_sparse_attn_fwd_kv2",
+           "svg_fp8_buffer_bytes", "svg_fp8_quantize", "svg_sparse_attn_fp8_fwd", "svg_qk_norm_rope",
+           "svg_probe_mfma_bf16")
 
 
 class SvgShape(C.Structure):
@@ -87,6 +89,10 @@ def lib():
         L.svg_sparse_attn_fwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.svg_sparse_attn_fwd_ex.restype = C.c_int
         L.svg_sparse_attn_fwd_ex.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_uint32, vp, C.c_size_t, vp]
+        L.svg_layout_kv_temporal.restype = C.c_int
+        L.svg_layout_kv_temporal.argtypes = [sp, vp, vp, vp, vp, vp, vp]
+        L.svg_sparse_attn_fwd_kv2.restype = C.c_int
+        L.svg_sparse_attn_fwd_kv2.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, C.c_uint32, vp]
         L.svg_qk_norm_rope.restype = C.c_int
         L.svg_qk_norm_rope.argtypes = [sp, vp, vp, C.c_int, vp, vp, C.c_float, vp, vp, C.c_int, vp]
         L.svg_fp8_buffer_bytes.restype = C.c_size_t
@@ -95,6 +101,8 @@ def lib():
         L.svg_fp8_quantize.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.svg_sparse_attn_fp8_fwd.restype = C.c_int
         L.svg_sparse_attn_fp8_fwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.svg_probe_mfma_bf16.restype = C.c_int
+        L.svg_probe_mfma_bf16.argtypes = [C.c_int, C.c_int32, C.c_int32, vp, vp, C.POINTER(C.c_double), vp]
         L.svg_dense_attn_fwd.restype = C.c_int
         L.svg_dense_attn_fwd.argtypes = [sp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         _lib = L
@@ -205,6 +213,18 @@ def svg_sparse_attn_fwd_ex(shape, q, k, v, o, labels, row_ptr_s, col_idx_s, row_
                                         int(workspace_bytes), _stream(stream)), "svg_sparse_attn_fwd_ex")
 
 
+def svg_layout_kv_temporal(shape, k, v, k_t, v_t, labels, stream=None):
+    _check(lib().svg_layout_kv_temporal(C.byref(shape), _ptr(k), _ptr(v), _ptr(k_t), _ptr(v_t), _ptr(labels),
+                                        _stream(stream)), "svg_layout_kv_temporal")
+
+
+def svg_sparse_attn_fwd_kv2(shape, q, k, v, k_t, v_t, o, labels, row_ptr_s, col_idx_s, row_ptr_t, col_idx_t,
+                            flags=0, stream=None):
+    _check(lib().svg_sparse_attn_fwd_kv2(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(k_t), _ptr(v_t), _ptr(o),
+                                         _ptr(labels), _ptr(row_ptr_s), _ptr(col_idx_s), _ptr(row_ptr_t),
+                                         _ptr(col_idx_t), int(flags), _stream(stream)), "svg_sparse_attn_fwd_kv2")
+
+
 def svg_dense_attn_fwd(shape, q, k, v, o, workspace=None, workspace_bytes=0, stream=None):
     _check(lib().svg_dense_attn_fwd(C.byref(shape), _ptr(q), _ptr(k), _ptr(v), _ptr(o),
                                     _ptr(workspace), int(workspace_bytes), _stream(stream)),
@@ -233,3 +253,11 @@ def svg_qk_norm_rope(shape, x, y, norm=SVG_NORM_NONE, weight=None, bias=None, ep
     _check(lib().svg_qk_norm_rope(C.byref(shape), _ptr(x), _ptr(y), int(norm), _ptr(weight), _ptr(bias),
                                   float(eps), _ptr(cos), _ptr(sin), int(pairing), _stream(stream)),
            "svg_qk_norm_rope")
+
+
+def svg_probe_mfma_bf16(form, workgroups, iterations, operands, sink, stream=None) -> float:
+    """Enqueues the matrix-core rate probe; returns the floating point operations of the launch."""
+    flop = C.c_double()
+    _check(lib().svg_probe_mfma_bf16(int(form), int(workgroups), int(iterations), _ptr(operands), _ptr(sink),
+                                     C.byref(flop), _stream(stream)), "svg_probe_mfma_bf16")
+    return flop.value

@@ -9,7 +9,7 @@ PKG_DIR = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 LIB_PATH = os.path.join(PKG_DIR, "libsvg_gfx950.so")
-SOURCES = ["svg_host.cpp", "svg_api.cpp", "svg_layout.hip", "svg_attn.hip", "svg_fp8.hip", "svg_qkrope.hip", "svg_static.hip"]
+SOURCES = ["svg_host.cpp", "svg_api.cpp", "svg_layout.hip", "svg_attn.hip", "svg_fp8.hip", "svg_qkrope.hip", "svg_static.hip", "svg_probe.hip"]
 
 
 def hipcc_path() -> str:

@@ -27,7 +27,7 @@ int layout_call(const svg_shape_t* shape, const void* in, void* out, const uint8
   if (rc != SVG_OK) return rc;
   if (!in || !out || svg::misaligned16(in) || svg::misaligned16(out)) return SVG_ERR_INVALID_ARG;
   if (overlap(in, out, tensor_bytes(g))) return SVG_ERR_ALIAS;
-  return svg::launch_layout(g, in, out, labels, inverse, static_cast<hipStream_t>(stream));
+  return svg::launch_layout(g, in, out, nullptr, nullptr, labels, inverse, false, static_cast<hipStream_t>(stream));
 }
 
 }  // namespace
@@ -75,9 +75,44 @@ int svg_sparse_attn_fwd_ex(const svg_shape_t* shape, const void* q, const void* 
   if (labels && (!row_ptr_t || !col_idx_t)) return SVG_ERR_INVALID_ARG;
   const size_t bytes = tensor_bytes(g);
   if (overlap(o, q, bytes) || overlap(o, k, bytes) || overlap(o, v, bytes)) return SVG_ERR_ALIAS;
-  return svg::launch_attention(g, q, k, v, o, labels, row_ptr_s, col_idx_s, row_ptr_t, col_idx_t,
+  return svg::launch_attention(g, q, k, v, nullptr, nullptr, o, labels, row_ptr_s, col_idx_s, row_ptr_t, col_idx_t,
                                true, (flags & SVG_ATTN_QO_TOKEN_ORDER) != 0,
                                (flags & SVG_ATTN_ELEMENT_MASK) != 0, static_cast<hipStream_t>(stream));
+}
+
+int svg_layout_kv_temporal(const svg_shape_t* shape, const void* k, const void* v, void* k_t, void* v_t,
+                           const uint8_t* labels, void* stream) {
+  Geo g;
+  int rc = svg::make_geo(shape, &g);
+  if (rc != SVG_OK) return rc;
+  if (!k || !v || !k_t || !v_t || !labels) return SVG_ERR_INVALID_ARG;
+  if (svg::misaligned16(k) || svg::misaligned16(v) || svg::misaligned16(k_t) || svg::misaligned16(v_t))
+    return SVG_ERR_INVALID_ARG;
+  const size_t bytes = tensor_bytes(g);
+  if (overlap(k_t, k, bytes) || overlap(k_t, v, bytes) || overlap(v_t, k, bytes) || overlap(v_t, v, bytes) ||
+      overlap(k_t, v_t, bytes))
+    return SVG_ERR_ALIAS;
+  return svg::launch_layout(g, k, k_t, v, v_t, labels, false, true, static_cast<hipStream_t>(stream));
+}
+
+int svg_sparse_attn_fwd_kv2(const svg_shape_t* shape, const void* q, const void* k, const void* v,
+                            const void* k_t, const void* v_t, void* o, const uint8_t* labels,
+                            const int32_t* row_ptr_s, const int32_t* col_idx_s, const int32_t* row_ptr_t,
+                            const int32_t* col_idx_t, uint32_t flags, void* stream) {
+  if (flags & ~(uint32_t)SVG_ATTN_ELEMENT_MASK) return SVG_ERR_INVALID_ARG;
+  Geo g;
+  int rc = svg::make_geo(shape, &g);
+  if (rc != SVG_OK) return rc;
+  rc = check_qkvo(q, k, v, o);
+  if (rc != SVG_OK) return rc;
+  if (!k_t || !v_t || svg::misaligned16(k_t) || svg::misaligned16(v_t)) return SVG_ERR_INVALID_ARG;
+  if (!labels || !row_ptr_s || !col_idx_s || !row_ptr_t || !col_idx_t) return SVG_ERR_INVALID_ARG;
+  const size_t bytes = tensor_bytes(g);
+  if (overlap(o, q, bytes) || overlap(o, k, bytes) || overlap(o, v, bytes) || overlap(o, k_t, bytes) ||
+      overlap(o, v_t, bytes))
+    return SVG_ERR_ALIAS;
+  return svg::launch_attention(g, q, k, v, k_t, v_t, o, labels, row_ptr_s, col_idx_s, row_ptr_t, col_idx_t, true,
+                               true, (flags & SVG_ATTN_ELEMENT_MASK) != 0, static_cast<hipStream_t>(stream));
 }
 
 int svg_sparse_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, const void* v,
@@ -100,7 +135,7 @@ int svg_dense_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, c
   if (rc != SVG_OK) return rc;
   const size_t bytes = tensor_bytes(g);
   if (overlap(o, q, bytes) || overlap(o, k, bytes) || overlap(o, v, bytes)) return SVG_ERR_ALIAS;
-  return svg::launch_attention(g, q, k, v, o, nullptr, nullptr, nullptr, nullptr, nullptr, false,
+  return svg::launch_attention(g, q, k, v, nullptr, nullptr, o, nullptr, nullptr, nullptr, nullptr, nullptr, false,
                                false, false, static_cast<hipStream_t>(stream));
 }
 

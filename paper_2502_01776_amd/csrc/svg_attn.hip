@@ -163,8 +163,6 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   const int r = lane & 31;       // query column within the wave / row of the A operand
 
   const size_t head = (size_t)bh * a.N;
-  const __bf16* kh = a.k + head * D;
-  const __bf16* vh = a.v + head * D;
 
   // ======================================================================================
   // This lane's query row, its mask window (profile), and Q^T as the B operand.
@@ -212,6 +210,11 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   // head that this lane reads and writes is the token whose transformed position is qrow
   // (Sec. 4.2: position off + p F + f holds token off + f P + p)
   const int pat = SPARSE && a.labels ? (a.labels[bh] != 0) : 0;
+  // a temporal head reads the P-outer copies of k and v when the caller keeps them apart from
+  // the originals (which the spatial heads read in place)
+  const bool kv_copy = SPARSE && __builtin_amdgcn_readfirstlane(pat) != 0 && a.k_t != nullptr;
+  const __bf16* kh = (kv_copy ? a.k_t : a.k) + head * D;
+  const __bf16* vh = (kv_copy ? a.v_t : a.v) + head * D;
   int io_row = qrow;
   if (SPARSE && a.qo_token_order && pat && qrow >= a.off && qrow < a.video_end) {
     const int vq = qrow - a.off;
@@ -957,11 +960,13 @@ AttnArgs base_args(const Geo& g, const void* q, const void* k, const void* v, vo
 
 }  // namespace
 
-int launch_attention(const Geo& g, const void* q, const void* k, const void* v, void* o,
-                     const uint8_t* labels, const int32_t* row_ptr_s, const int32_t* col_idx_s,
+int launch_attention(const Geo& g, const void* q, const void* k, const void* v, const void* k_t, const void* v_t,
+                     void* o, const uint8_t* labels, const int32_t* row_ptr_s, const int32_t* col_idx_s,
                      const int32_t* row_ptr_t, const int32_t* col_idx_t, bool sparse,
                      bool qo_token_order, bool element_mask, hipStream_t stream) {
   AttnArgs a = base_args(g, q, k, v, o);
+  a.k_t = static_cast<const __bf16*>(k_t);
+  a.v_t = static_cast<const __bf16*>(v_t);
   a.labels = labels;
   a.qo_token_order = sparse && qo_token_order ? 1 : 0;
   a.row_ptr[0] = row_ptr_s; a.col_idx[0] = col_idx_s;

@@ -24,6 +24,8 @@ struct AttnArgs {
   const __bf16* q;
   const __bf16* k;
   const __bf16* v;
+  const __bf16* k_t;          // sparse: P-outer copies of k and v read by temporal heads instead of k, v; may be null
+  const __bf16* v_t;
   void* o;                    // bf16 [B,H,N,D] (dense, sparse) or fp32 [3][BH][t][D] (profile)
   const uint8_t* labels;      // sparse: per-head pattern, may be null
   const int32_t* row_ptr[2];

@@ -55,10 +55,13 @@ inline int hip_status(hipError_t e) {
 }
 
 // Kernel launchers (defined in the .hip files).  All arguments validated by the caller.
-int launch_layout(const Geo& g, const void* in, void* out, const uint8_t* labels, bool inverse,
-                  hipStream_t stream);
-int launch_attention(const Geo& g, const void* q, const void* k, const void* v, void* o,
-                     const uint8_t* labels, const int32_t* row_ptr_s, const int32_t* col_idx_s,
+// in2 / out2: optional second tensor moved by the same launch; temporal_only: heads labelled
+// spatial are skipped instead of copied
+int launch_layout(const Geo& g, const void* in, void* out, const void* in2, void* out2, const uint8_t* labels,
+                  bool inverse, bool temporal_only, hipStream_t stream);
+// k_t / v_t: optional P-outer copies of k and v that heads labelled temporal read instead of k / v
+int launch_attention(const Geo& g, const void* q, const void* k, const void* v, const void* k_t, const void* v_t,
+                     void* o, const uint8_t* labels, const int32_t* row_ptr_s, const int32_t* col_idx_s,
                      const int32_t* row_ptr_t, const int32_t* col_idx_t, bool sparse,
                      bool qo_token_order, bool element_mask, hipStream_t stream);
 int launch_profile(const Geo& g, const void* q, const void* k, const void* v, const int32_t* rows,

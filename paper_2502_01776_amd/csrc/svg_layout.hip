@@ -16,9 +16,10 @@ constexpr int kThreads = 256;
 constexpr int kRowsPerThread = 4;   // independent 16-byte loads in flight per thread
 
 struct LayoutArgs {
-  const u32x4* in;
-  u32x4* out;
+  const u32x4* in[2];      // one or two tensors per launch (blockIdx.z)
+  u32x4* out[2];
   const uint8_t* labels;
+  int temporal_only;       // heads labelled spatial are left alone (their slots of `out` are not written)
   int N, off, video_end, F, P;
   int chunks_log2;     // log2(D/8): 16-byte pieces per row
   int inverse;
@@ -44,6 +45,9 @@ __global__ __launch_bounds__(kThreads) void layout_kernel(LayoutArgs a) {
   const int lane_row = threadIdx.x >> a.chunks_log2;
   const int c = threadIdx.x & (cpr - 1);
   const bool permute = a.labels == nullptr || a.labels[bh] == SVG_HEAD_TEMPORAL;
+  if (a.temporal_only && !permute) return;
+  const u32x4* in = a.in[blockIdx.z];
+  u32x4* out = a.out[blockIdx.z];
   const size_t head = (size_t)bh * a.N;
   const int row0 = blockIdx.x * (rows_per_pass * kRowsPerThread) + lane_row;
 
@@ -53,29 +57,32 @@ __global__ __launch_bounds__(kThreads) void layout_kernel(LayoutArgs a) {
     const int n = row0 + i * rows_per_pass;
     if (n < a.N) {
       const int src = permute ? source_row(a, n) : n;
-      val[i] = __builtin_nontemporal_load(&a.in[((head + src) << a.chunks_log2) + c]);
+      val[i] = __builtin_nontemporal_load(&in[((head + src) << a.chunks_log2) + c]);
     }
   }
 #pragma unroll
   for (int i = 0; i < kRowsPerThread; ++i) {
     const int n = row0 + i * rows_per_pass;
-    if (n < a.N) __builtin_nontemporal_store(val[i], &a.out[((head + n) << a.chunks_log2) + c]);
+    if (n < a.N) __builtin_nontemporal_store(val[i], &out[((head + n) << a.chunks_log2) + c]);
   }
 }
 
 }  // namespace
 
-int launch_layout(const Geo& g, const void* in, void* out, const uint8_t* labels, bool inverse,
-                  hipStream_t stream) {
+int launch_layout(const Geo& g, const void* in, void* out, const void* in2, void* out2, const uint8_t* labels,
+                  bool inverse, bool temporal_only, hipStream_t stream) {
   LayoutArgs a;
-  a.in = static_cast<const u32x4*>(in);
-  a.out = static_cast<u32x4*>(out);
+  a.in[0] = static_cast<const u32x4*>(in);
+  a.out[0] = static_cast<u32x4*>(out);
+  a.in[1] = static_cast<const u32x4*>(in2);
+  a.out[1] = static_cast<u32x4*>(out2);
+  a.temporal_only = temporal_only ? 1 : 0;
   a.labels = labels;
   a.N = g.N; a.off = g.off; a.video_end = g.video_end; a.F = g.F; a.P = g.P;
   a.chunks_log2 = g.D == 128 ? 4 : 3;
   a.inverse = inverse ? 1 : 0;
   const int rows_per_block = (kThreads >> a.chunks_log2) * kRowsPerThread;
-  dim3 grid((g.N + rows_per_block - 1) / rows_per_block, g.B * g.H);
+  dim3 grid((g.N + rows_per_block - 1) / rows_per_block, g.B * g.H, in2 ? 2 : 1);
   if (grid.y > 65535u) return SVG_ERR_UNSUPPORTED;
   (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
   hipLaunchKernelGGL(layout_kernel, grid, dim3(kThreads), 0, stream, a);

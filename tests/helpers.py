@@ -65,6 +65,20 @@ def gpu_layer_token_order(shape, q, k, v, labels, lists=None):
     return o
 
 
+def gpu_layer_kv2(shape, q, k, v, labels, lists=None, flags=0, fill=None):
+    """k, v of the temporal heads only -> P-outer copies (one launch) -> block-sparse attention that
+    reads the originals for spatial heads; q and o in token order.  Returns (o, k_t, v_t)."""
+    lists = lists or device_tile_lists(shape)
+    kt, vt, o = (torch.empty_like(q) for _ in range(3))
+    if fill is not None:
+        kt.view(torch.int16).fill_(fill)
+        vt.view(torch.int16).fill_(fill)
+    S.svg_layout_kv_temporal(shape, k, v, kt, vt, labels)
+    S.svg_sparse_attn_fwd_kv2(shape, q, k, v, kt, vt, o, labels, *lists, flags=flags)
+    torch.cuda.synchronize()
+    return o, kt, vt
+
+
 def assert_attn_close(got: torch.Tensor, ref: np.ndarray, what=""):
     g = f64(got)
     assert np.isfinite(g).all(), f"{what}: non-finite output"

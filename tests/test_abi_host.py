@@ -187,6 +187,23 @@ def test_pointer_checks_without_gpu():
     assert lib.svg_layout_fwd(C.byref(sh), a, a, None, None) == -4
     assert lib.svg_layout_inv(C.byref(sh), a, a + nbytes - 16, None, None) == -4
     assert lib.svg_dense_attn_fwd(C.byref(sh), a, a, a, a, None, 0, None) == -4
+    # the two-source sparse pass and the temporal-only layout of k and v
+    far = [a + i * (1 << 32) for i in range(8)]          # q k v k_t v_t o: far apart
+    q_, k_, v_, kt_, vt_, o_ = far[:6]
+    kv2 = lambda *args: lib.svg_sparse_attn_fwd_kv2(C.byref(sh), *args)
+    assert kv2(q_, k_, v_, None, vt_, o_, a, a, a, a, a, 0, None) == -1
+    assert kv2(q_, k_, v_, kt_, vt_, o_, None, a, a, a, a, 0, None) == -1          # labels are required
+    assert kv2(q_, k_, v_, kt_, vt_, o_, a, a, a, None, a, 0, None) == -1
+    assert kv2(q_, k_, v_, kt_, vt_, o_, a, a, a, a, a, 1, None) == -1             # token order is implied, not a flag
+    assert kv2(q_, k_, v_, kt_, vt_, kt_ + 32, a, a, a, a, a, 0, None) == -4
+    assert kv2(q_, k_, v_, kt_, vt_, q_, a, a, a, a, a, 2, None) == -4
+    lkv = lambda *args: lib.svg_layout_kv_temporal(C.byref(sh), *args)
+    assert lkv(k_, v_, kt_, None, a, None) == -1
+    assert lkv(k_, v_, kt_, vt_, None, None) == -1
+    assert lkv(k_, v_, kt_ + 4, vt_, a, None) == -1
+    assert lkv(k_, v_, k_, vt_, a, None) == -4
+    assert lkv(k_, v_, kt_, kt_ + nbytes - 16, a, None) == -4
+    assert lkv(k_, v_, v_ + 16, vt_, a, None) == -4
     # workspace
     need = S.svg_workspace_bytes(sh, 24)
     # one key range for this small shape: 3 outputs + 1 set of row statistics + row order

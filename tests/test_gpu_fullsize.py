@@ -9,7 +9,7 @@ import torch
 import paper_2502_01776_amd as S
 from oracle import svg_oracle as O
 from workloads import get_config, make_qkv, sample_rows, planted_labels
-from helpers import f64, bits, dev_i32, device_tile_lists, gpu_profile, assert_attn_close, labels_match
+from helpers import f64, bits, dev_i32, device_tile_lists, gpu_profile, gpu_layer_kv2, assert_attn_close, labels_match
 
 pytestmark = pytest.mark.gpu
 
@@ -40,13 +40,17 @@ def test_full_size_layer_sampled(name):
     assert np.array_equal(lab, planted_labels(cfg)), "profiled labels differ from the planted ones"
     nq, nk = O.n_tiles(g)
 
-    # the pipeline bench.py times (q read and o written in token order by the attention kernel
-    # itself) gives the same bits as the four-pass pipeline checked below
+    # the pipeline bench.py times (k and v of the temporal heads moved by one launch, spatial heads
+    # read in place, q read and o written in token order by the attention kernel itself) gives
+    # the same bits as the four-pass pipeline checked below; so does the form with all of k, v moved
     o2 = torch.empty_like(o)
     S.svg_sparse_attn_fwd_ex(sh, q, kp, vp, o2, labels, *device_tile_lists(sh), flags=S.SVG_ATTN_QO_TOKEN_ORDER)
     torch.cuda.synchronize()
     assert torch.equal(o2.view(torch.int16), o.view(torch.int16))
     del o2
+    o3, kt, vt = gpu_layer_kv2(sh, q, k, v, labels)
+    assert torch.equal(o3.view(torch.int16), o.view(torch.int16))
+    del o3, kt, vt
 
     # profiling: the errors and labels that THIS launch (all heads, all sampled rows, the key-range
     # split and row ordering of the full-size configuration) wrote for one head of each label,

@@ -8,7 +8,7 @@ import paper_2502_01776_amd as S
 from oracle import svg_oracle as O
 from workloads import get_config, make_qkv, make_plain_qkv, sample_rows, planted_labels
 from helpers import (f64, bits, dev_i32, device_tile_lists, gpu_profile, gpu_layer, gpu_layer_token_order,
-                     assert_attn_close,
+                     gpu_layer_kv2, assert_attn_close,
                      labels_match)
 
 pytestmark = pytest.mark.gpu
@@ -266,6 +266,47 @@ def test_layer_with_q_and_o_in_token_order(name, sink):
     ones = torch.ones_like(labels)
     assert torch.equal(gpu_layer_token_order(sh, qc, kc, vc, ones).view(torch.int16),
                        gpu_layer(sh, qc, kc, vc, ones).view(torch.int16))
+
+
+@pytest.mark.parametrize("name", SMALL)
+@pytest.mark.parametrize("sink", [0, 1])
+def test_layer_with_only_temporal_kv_moved(name, sink):
+    """svg_layout_kv_temporal + svg_sparse_attn_fwd_kv2: k and v of spatial heads are read in place and
+    never copied; against the oracle, bit-identical to the four-pass pipeline, and the slots of
+    spatial heads in the copies are neither written nor (NaN filled) read."""
+    cfg, sh, g = setup(name, sink_first_frame=sink)
+    q, k, v = make_qkv(cfg)
+    qc, kc, vc = q.cuda(), k.cuda(), v.cuda()
+    lab_np = planted_labels(cfg)
+    labels = torch.from_numpy(lab_np).cuda()
+    NAN = 0x7FC1                   # a bf16 NaN pattern, as int16
+    o, kt, vt = gpu_layer_kv2(sh, qc, kc, vc, labels, fill=NAN)
+    assert torch.isfinite(o.float()).all()
+    ref = O.svg_attention_layer(f64(q), f64(k), f64(v), lab_np.reshape(g.B, g.H), g)
+    for b in range(g.B):
+        for h in range(g.H):
+            assert_attn_close(o[b, h], ref[b, h], f"{name} kv2 layer b{b} h{h}")
+            slot_k, slot_v = kt[b, h].view(torch.int16), vt[b, h].view(torch.int16)
+            if lab_np[b * g.H + h] == O.SPATIAL:
+                assert (slot_k == NAN).all() and (slot_v == NAN).all()
+            else:
+                assert np.array_equal(bits(kt[b, h]), O.layout_fwd(bits(kc[b, h]), g))
+                assert np.array_equal(bits(vt[b, h]), O.layout_fwd(bits(vc[b, h]), g))
+    o4 = gpu_layer(sh, qc, kc, vc, labels)
+    assert torch.equal(o.view(torch.int16), o4.view(torch.int16))
+    # with the element mask on it equals the flag on the extended entry point
+    oe, _, _ = gpu_layer_kv2(sh, qc, kc, vc, labels, flags=S.SVG_ATTN_ELEMENT_MASK)
+    kp, vp, oe2 = (torch.empty_like(qc) for _ in range(3))
+    S.svg_layout_fwd(sh, kc, kp, labels)
+    S.svg_layout_fwd(sh, vc, vp, labels)
+    S.svg_sparse_attn_fwd_ex(sh, qc, kp, vp, oe2, labels, *device_tile_lists(sh),
+                             flags=S.SVG_ATTN_QO_TOKEN_ORDER | S.SVG_ATTN_ELEMENT_MASK)
+    torch.cuda.synchronize()
+    assert torch.equal(oe.view(torch.int16), oe2.view(torch.int16))
+    with pytest.raises(S.SvgError):
+        S.svg_sparse_attn_fwd_kv2(sh, qc, kc, vc, kt, vt, o, labels, *device_tile_lists(sh), flags=1)
+    with pytest.raises(S.SvgError):
+        S.svg_layout_kv_temporal(sh, kc, vc, kt, kt, labels)           # the two copies overlap
 
 
 def test_extended_entry_point_rejects_unknown_flags():
