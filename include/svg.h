@@ -15,7 +15,11 @@
  *     [B, H, N, D], N = F*P + T, 16-byte aligned.  A video token of frame f and
  *     in-frame position p sits at row off + f*P + p ("F-outer" order), where
  *     off = T if text_first else 0; the T text tokens occupy [0,T) or [F*P,N).
- *     The transformed ("P-outer") order puts that token at row off + p*F + f.
+ *     The transformed ("P-outer") order puts that token at row off + p*F + f.  With
+ *     sink_first_frame set it keeps frame 0 together instead: row off + p for f = 0 and
+ *     row off + P + p*(F-1) + (f-1) for the other frames, so that the first-frame keys,
+ *     which every query keeps (Sec. 3.1), are ceil(P/block_n) contiguous key tiles for a
+ *     temporal head as well.
  *   - All pointers are owned by the caller.  The library allocates no device
  *     memory, keeps no state between calls, and never synchronises the host:
  *     kernels are enqueued on `stream` (a hipStream_t passed as void*, NULL = the

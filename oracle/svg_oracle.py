@@ -17,7 +17,8 @@ Readings taken where the paper is silent (each listed in the design notes):
     |f_i - f_j| <= w_s and |p_i - p_j| <= w_t (Sec. 3.1, Sec. 3.3);
   * text keys are kept by both patterns and text queries attend to everything
     (Sec. 3.1, last paragraph); the first-frame keys are kept only when the
-    geometry's sink flag is set;
+    geometry's sink flag is set, and then the transformed order of a temporal head
+    keeps frame 0 as one block (see layout_perm);
   * the per-head error is the mean over (sampled row, channel) of the squared
     difference, and a head is spatial iff MSE_s < MSE_t strictly (Alg. 1);
   * the block-sparse pass keeps a (query tile, key tile) pair iff at least one of
@@ -142,11 +143,20 @@ def masked_attention(q, k, v, mask, scale: float, weight_round=None) -> np.ndarr
 # layout transformation (Sec. 4.2, Fig. 4)
 # ----------------------------------------------------------------------------
 def layout_perm(g: Geometry) -> np.ndarray:
-    """pi[n] = index in the P-outer order of the token at index n in the F-outer
-    order.  Text tokens stay where they are."""
+    """pi[n] = index in the transformed (P-outer) order of the token at index n in the
+    F-outer order.  Text tokens stay where they are.  With the first-frame sink on
+    (Sec. 3.1: the first frame is attended by every query of both head types) the
+    transformed order keeps the P tokens of frame 0 together, in position order, in front of
+    the video part, and runs the position-outer order over the other F - 1 frames only:
+    every query keeps all of frame 0, and as one contiguous run it costs ceil(P / block_n)
+    key tiles instead of touching every tile (its tokens would otherwise sit F rows apart)."""
     is_text, frame, pos = token_coords(g)
     n = np.arange(g.N)
-    return np.where(is_text, n, g.off + pos * g.F + frame)
+    if g.sink_first_frame:
+        video = np.where(frame == 0, pos, g.P + pos * (g.F - 1) + (frame - 1))
+    else:
+        video = pos * g.F + frame
+    return np.where(is_text, n, g.off + video)
 
 
 def layout_fwd(x: np.ndarray, g: Geometry) -> np.ndarray:

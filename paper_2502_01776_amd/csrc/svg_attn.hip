@@ -208,7 +208,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
 
   // sparse: this head's pattern; with q and o kept in token order, the row of a temporal
   // head that this lane reads and writes is the token whose transformed position is qrow
-  // (Sec. 4.2: position off + p F + f holds token off + f P + p)
+  // (Sec. 4.2: position off + p F + f holds token off + f P + p; with the first-frame sink,
+  // frame 0 leads as a block)
   const int pat = SPARSE && a.labels ? (a.labels[bh] != 0) : 0;
   // a temporal head reads the P-outer copies of k and v when the caller keeps them apart from
   // the originals (which the spatial heads read in place)
@@ -216,16 +217,18 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   const __bf16* kh = (kv_copy ? a.k_t : a.k) + head * D;
   const __bf16* vh = (kv_copy ? a.v_t : a.v) + head * D;
   int io_row = qrow;
-  if (SPARSE && a.qo_token_order && pat && qrow >= a.off && qrow < a.video_end) {
-    const int vq = qrow - a.off;
-    const int p = vq / a.F;
-    io_row = a.off + (vq - p * a.F) * a.P + p;
-  }
+  if (SPARSE && a.qo_token_order && pat && qrow >= a.off && qrow < a.video_end)
+    io_row = a.off + (int)transformed_to_token((unsigned)(qrow - a.off), (unsigned)a.F, (unsigned)a.P, a.sink);
   if (MODE == kSparseExact && qrow >= a.off && qrow < a.video_end) {
     // element mask of the head's pattern in the order its tile list refers to: a spatial head
     // compares frames (coordinate = row / P), a temporal head in P-outer order compares in-frame
     // positions (coordinate = row / F); text queries keep the default window (everything)
-    const int cq = (qrow - a.off) / (pat ? a.F : a.P);
+    int cq = (qrow - a.off) / a.P;
+    if (pat) {
+      unsigned pq;
+      transformed_to_token((unsigned)(qrow - a.off), (unsigned)a.F, (unsigned)a.P, a.sink, &pq);
+      cq = (int)pq;
+    }
     const int w = pat ? a.w_t : a.w_s;
     win_lo = cq - w;
     win_span = 2u * (unsigned)w;
@@ -504,10 +507,15 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
       } else if ((MODE == kProfile && variant == 0) || key < a.off || key >= a.video_end) {
         code = kCodeKeep;
       } else if (MODE == kSparseExact) {
-        const int vk = key - a.off;
-        const int hi = vk / (pat ? a.F : a.P);          // spatial: frame; P-outer temporal: position
-        code = hi;
-        const int fk = pat ? vk - hi * a.F : hi;          // the key's frame
+        // spatial: the key's frame; temporal (transformed order): its in-frame position
+        unsigned pk, fk;
+        if (pat) {
+          transformed_to_token((unsigned)(key - a.off), (unsigned)a.F, (unsigned)a.P, a.sink, &pk, &fk);
+        } else {
+          fk = (unsigned)(key - a.off) / (unsigned)a.P;
+          pk = fk;
+        }
+        code = (int)pk;
         if (a.sink && fk == 0) code = kCodeKeep;
       } else {
         const int vk = key - a.off;

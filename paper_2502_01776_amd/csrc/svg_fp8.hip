@@ -100,7 +100,7 @@ struct QuantArgs {
   float* scales;               // [3][BH]
   const unsigned* amax;        // [3][BH] fp32 bits
   const uint8_t* labels;
-  int N, BH, off, video_end, F, P;
+  int N, BH, off, video_end, F, P, sink;
 };
 
 // One workgroup converts one 64-row tile of one head of one tensor.
@@ -129,9 +129,7 @@ __global__ __launch_bounds__(256) void fp8_quantize_kernel(QuantArgs a) {
     if (m < a.N) {
       int s = m;
       if (permute && m >= a.off && m < a.video_end) {
-        const unsigned vv = (unsigned)(m - a.off);
-        const unsigned p = vv / (unsigned)a.F, f = vv - p * (unsigned)a.F;
-        s = a.off + (int)(f * (unsigned)a.P + p);
+        s = a.off + (int)transformed_to_token((unsigned)(m - a.off), (unsigned)a.F, (unsigned)a.P, a.sink);
       }
       x = __builtin_nontemporal_load(&src[(size_t)s * (kD / 8) + c]);
     }
@@ -200,7 +198,7 @@ struct Fp8Args {
   const int32_t* col_idx[2];
   int N, nk, BH, nqt, total, reverse_q;
   float scale_log2;            // softmax scale * log2(e), before the quantisation scales
-  int off, video_end, F, P;
+  int off, video_end, F, P, sink;
 };
 
 __global__ __launch_bounds__(256, 2) void attn_fp8_kernel(Fp8Args a) {
@@ -228,11 +226,8 @@ __global__ __launch_bounds__(256, 2) void attn_fp8_kernel(Fp8Args a) {
   const int qslot = grp * kBM + wave * 32 + r;
   const int qrow = min(qslot, a.N - 1);
   int io_row = qrow;
-  if (pat && qrow >= a.off && qrow < a.video_end) {
-    const int vq = qrow - a.off;
-    const int p = vq / a.F;
-    io_row = a.off + (vq - p * a.F) * a.P + p;
-  }
+  if (pat && qrow >= a.off && qrow < a.video_end)
+    io_row = a.off + (int)transformed_to_token((unsigned)(qrow - a.off), (unsigned)a.F, (unsigned)a.P, a.sink);
   i32x8 qreg[2];       // lane (g, r) holds channels 64 s + 32 g .. + 32 of its query
   {
     const unsigned char* qp = a.q8 + ((size_t)bh * a.N + io_row) * kD + g * 32;
@@ -488,7 +483,7 @@ int launch_fp8_quantize(const Geo& g, const void* q, const void* k, const void* 
   a.scales = scales;
   a.amax = amax;
   a.labels = labels;
-  a.N = g.N; a.BH = BH; a.off = g.off; a.video_end = g.video_end; a.F = g.F; a.P = g.P;
+  a.N = g.N; a.BH = BH; a.off = g.off; a.video_end = g.video_end; a.F = g.F; a.P = g.P; a.sink = g.sink;
   hipLaunchKernelGGL(fp8_quantize_kernel, dim3(g.nk, BH, 3), dim3(256), 0, stream, a);
   return hip_status(hipGetLastError());
 }
@@ -510,7 +505,7 @@ int launch_fp8_attention(const Geo& g, const void* q8, const void* k8, const voi
   a.total = a.BH * a.nqt;
   a.reverse_q = (g.T > 0 && !g.text_first) ? 1 : 0;
   a.scale_log2 = g.scale * 1.4426950408889634f;
-  a.off = g.off; a.video_end = g.video_end; a.F = g.F; a.P = g.P;
+  a.off = g.off; a.video_end = g.video_end; a.F = g.F; a.P = g.P; a.sink = g.sink;
   const unsigned grid = 8u * (unsigned)((a.total + 7) / 8);
   (void)hipGetLastError();
   hipLaunchKernelGGL(attn_fp8_kernel, dim3(grid), dim3(256), 0, stream, a);

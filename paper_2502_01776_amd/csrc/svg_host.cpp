@@ -107,17 +107,10 @@ int svg_tile_list_build(const svg_shape_t* shape, int pattern, int32_t* row_ptr,
   if (g.T > 0) {
     if (g.text_first) mark(always, 0, g.T - 1); else mark(always, v1, g.N - 1);
   }
-  if (g.sink) {
-    if (pattern == SVG_HEAD_SPATIAL || frame_major_temporal) {
-      mark(always, v0, v0 + g.P - 1);
-    } else {
-      for (int b = 0; b < g.nk; ++b) {  // P-outer: frame-0 tokens sit at video offsets k*F
-        int64_t lo = std::max<int64_t>((int64_t)b * g.bn, v0) - v0;
-        int64_t hi = std::min<int64_t>((int64_t)(b + 1) * g.bn, v1) - 1 - v0;
-        if (lo <= hi && ((lo + g.F - 1) / g.F) * g.F <= hi) always[b] = 1;
-      }
-    }
-  }
+  // first-frame sink: in every order frame 0 is the first P video rows (the transformed order of a
+  // temporal head keeps it as a block in front, see transformed_to_token)
+  if (g.sink) mark(always, v0, v0 + g.P - 1);
+  const bool sink_temporal = g.sink && pattern == SVG_HEAD_TEMPORAL;
 
   int64_t nnz = 0;
   bool overflow = false;
@@ -148,6 +141,21 @@ int svg_tile_list_build(const svg_shape_t* shape, int pattern, int32_t* row_ptr,
         keep_positions(pa, g.P - 1);
         keep_positions(0, pb);
       }
+    } else if (sink_temporal) {
+      // Transformed order with the sink: rows [v0, v0 + P) are frame 0 in position order, rows from
+      // b0 = v0 + P on hold positions outer over the other F - 1 frames.  Frame-0 keys are kept
+      // anyway; of the others a query at position p keeps the positions within w_t of it.  The
+      // tile's rows may lie in either part or in both.
+      keep = always;
+      const int64_t b0 = v0 + g.P, rest = g.F - 1;
+      auto keep_positions = [&](int64_t lo, int64_t hi) {
+        if (rest <= 0) return;
+        lo = std::max<int64_t>(0, lo - g.w_t);
+        hi = std::min<int64_t>(g.P - 1, hi + g.w_t);
+        mark(keep, b0 + lo * rest, b0 + (hi + 1) * rest - 1);
+      };
+      if (r0 < b0) keep_positions(r0 - v0, std::min<int64_t>(r1, b0 - 1) - v0);
+      if (r1 >= b0 && rest > 0) keep_positions((std::max<int64_t>(r0, b0) - b0) / rest, (r1 - b0) / rest);
     } else {
       keep = always;
       const int64_t ga = (r0 - v0) / unit, gb = (r1 - v0) / unit;

@@ -34,6 +34,39 @@ inline size_t profile_workspace_bytes(const Geo& g, int t) {
          bh * (size_t)((t + 15) / 16) * 2 * sizeof(float) + (((size_t)t * 4 + 15) & ~(size_t)15);
 }
 
+// The transformed ("P-outer") order of a temporal head, video part only; offsets are relative
+// to the first video row.  Without the first-frame sink the token of frame f and position p
+// sits at offset p*F + f (Sec. 4.2).  With the sink on (Sec. 3.1: every query also attends
+// to the first frame) frame 0 comes first as one block in position order (offset p), and the
+// position-outer order runs over the other frames: offset P + p*(F-1) + (f-1); the frame-0
+// keys are then one contiguous run of key tiles instead of one key in every F rows.
+// transformed_to_token returns the F-outer offset f*P + p of the token at transformed offset v.
+__host__ __device__ inline unsigned transformed_to_token(unsigned v, unsigned F, unsigned P, int sink,
+                                                         unsigned* pos = nullptr, unsigned* frame = nullptr) {
+  unsigned p, f;
+  if (sink) {
+    if (v < P) {
+      p = v;
+      f = 0;
+    } else {
+      const unsigned w = v - P, rest = F > 1 ? F - 1 : 1;
+      p = w / rest;
+      f = w - p * rest + 1;
+    }
+  } else {
+    p = v / F;
+    f = v - p * F;
+  }
+  if (pos) *pos = p;
+  if (frame) *frame = f;
+  return f * P + p;
+}
+__host__ __device__ inline unsigned token_to_transformed(unsigned v, unsigned F, unsigned P, int sink) {
+  const unsigned f = v / P, p = v - f * P;
+  if (sink) return f == 0 ? p : P + p * (F - 1) + (f - 1);
+  return p * F + f;
+}
+
 inline bool misaligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
 // Argument checks shared by the profiling entry points (everything except the workspace).

@@ -20,7 +20,7 @@ struct LayoutArgs {
   u32x4* out[2];
   const uint8_t* labels;
   int temporal_only;       // heads labelled spatial are left alone (their slots of `out` are not written)
-  int N, off, video_end, F, P;
+  int N, off, video_end, F, P, sink;
   int chunks_log2;     // log2(D/8): 16-byte pieces per row
   int inverse;
 };
@@ -29,13 +29,9 @@ struct LayoutArgs {
 __device__ __forceinline__ int source_row(const LayoutArgs& a, int n) {
   if (n < a.off || n >= a.video_end) return n;         // text rows stay
   const unsigned v = (unsigned)(n - a.off);
-  if (!a.inverse) {            // out is P-outer: v = p*F + f  <-  in row f*P + p
-    const unsigned p = v / (unsigned)a.F, f = v - p * (unsigned)a.F;
-    return a.off + (int)(f * (unsigned)a.P + p);
-  } else {                     // out is F-outer: v = f*P + p  <-  in row p*F + f
-    const unsigned f = v / (unsigned)a.P, p = v - f * (unsigned)a.P;
-    return a.off + (int)(p * (unsigned)a.F + f);
-  }
+  if (!a.inverse)              // out is in the transformed order: row v  <-  that row's token
+    return a.off + (int)transformed_to_token(v, (unsigned)a.F, (unsigned)a.P, a.sink);
+  return a.off + (int)token_to_transformed(v, (unsigned)a.F, (unsigned)a.P, a.sink);   // out is F-outer
 }
 
 __global__ __launch_bounds__(kThreads) void layout_kernel(LayoutArgs a) {
@@ -78,7 +74,7 @@ int launch_layout(const Geo& g, const void* in, void* out, const void* in2, void
   a.out[1] = static_cast<u32x4*>(out2);
   a.temporal_only = temporal_only ? 1 : 0;
   a.labels = labels;
-  a.N = g.N; a.off = g.off; a.video_end = g.video_end; a.F = g.F; a.P = g.P;
+  a.N = g.N; a.off = g.off; a.video_end = g.video_end; a.F = g.F; a.P = g.P; a.sink = g.sink;
   a.chunks_log2 = g.D == 128 ? 4 : 3;
   a.inverse = inverse ? 1 : 0;
   const int rows_per_block = (kThreads >> a.chunks_log2) * kRowsPerThread;

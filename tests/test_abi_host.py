@@ -80,6 +80,21 @@ def test_host_tile_list_sampled_rows_at_full_size(name):
             assert np.array_equal(ci[rp[a]:rp[a + 1]], O.kept_tiles_of_row(g, pattern, a)), (pattern, a)
 
 
+def test_host_tile_list_with_first_frame_sink_at_full_size():
+    """Sink on at the 119k-token shape: sampled list rows against the oracle's brute force (incl. the
+    query tile in which the frame-0 block of the transformed order ends), and the kept fraction of a
+    temporal head stays far below the dense count it had with frame 0 spread over every F-th row."""
+    cfg = get_config("hunyuan_skip85", sink_first_frame=1)
+    sh, g = S.shape_from_config(cfg), O.Geometry.from_config(cfg)
+    nq, nk = S.svg_tile_counts(sh)
+    for pattern in (0, 1, 2):
+        rp, ci = S.svg_tile_list_build(sh, pattern)
+        for a in (0, g.P // g.block_m, nq // 2, nq - 1):
+            assert np.array_equal(ci[rp[a]:rp[a + 1]], O.kept_tiles_of_row(g, pattern, a)), (pattern, a)
+        if pattern != 2:
+            assert len(ci) < 0.2 * nq * nk
+
+
 def test_host_tile_counts_match_the_stored_ones():
     """All six benchmark shapes against tests/golden/tile_counts.txt (written from the oracle by
     tests/golden/make_tile_counts.py)."""

@@ -100,6 +100,55 @@ def test_full_size_layer_sampled(name):
             assert np.array_equal(bits(o[0, h]), bits(op[0, h]))
 
 
+def test_full_size_first_frame_sink_stays_sparse():
+    """Sec. 3.1 keeps the first frame in both patterns.  At the 119k-token shape with the sink on:
+    the kept-tile fraction stays under 20 % for both head types (the transformed order holds frame 0
+    as one block), the block-sparse pass matches the oracle on sampled query tiles, and the pass
+    with the element mask matches the oracle's masked attention (the masks of Sec. 3.1 themselves,
+    original token order) on sampled query rows."""
+    cfg = get_config("hunyuan_skip85", sink_first_frame=1)
+    g = O.Geometry.from_config(cfg)
+    sh = S.shape_from_config(cfg)
+    nq, nk = O.n_tiles(g)
+    nnz = [len(S.svg_tile_list_build(sh, pat)[1]) for pat in (0, 1)]
+    frac = [n / (nq * nk) for n in nnz]
+    print(f"kept-tile fraction with the first-frame sink: spatial {frac[0]:.4f}, temporal {frac[1]:.4f}")
+    assert 0.15 < frac[0] < 0.20 and 0.15 < frac[1] < 0.20
+    q, k, v = make_qkv(cfg, device="cuda")
+    lab = planted_labels(cfg)
+    labels = torch.from_numpy(lab).cuda()
+    lists = device_tile_lists(sh)
+    o, kt, vt = gpu_layer_kv2(sh, q, k, v, labels, lists)
+    oe, _, _ = gpu_layer_kv2(sh, q, k, v, labels, lists, flags=S.SVG_ATTN_ELEMENT_MASK)
+    del kt, vt
+    tiles = sorted({0, 1, g.P // g.block_m, nq // 2, nq - 3, nq - 1})      # incl. the tile where the frame-0 block ends
+    edge = g.off + g.F * g.P
+    rows = np.array(sorted({0, 1, g.P - 1, g.P, g.P + 1, 7 * g.P + 1234, 16 * g.P + 3599, 32 * g.P + 5, edge - 1, edge,
+                            g.N - 1}))
+    perm = O.layout_perm(g)
+    for h in (int(np.nonzero(lab == O.SPATIAL)[0][0]), int(np.nonzero(lab == O.TEMPORAL)[0][0])):
+        pat = int(lab[h])
+        qh, kh, vh = f64(q[0, h]), f64(k[0, h]), f64(v[0, h])
+        # exact masks, original order
+        mask = O.spatial_mask(g, rows) if pat == O.SPATIAL else O.temporal_mask(g, rows)
+        ref = O.masked_attention(qh[rows], kh, vh, mask, g.scale)
+        assert_attn_close(oe[0, h][rows], ref, f"sink, exact mask, head {h}")
+        # block cover, in the order the tile list refers to
+        got = f64(o[0, h])
+        if pat == O.TEMPORAL:
+            qh, kh, vh, got = (O.layout_fwd(x, g) for x in (qh, kh, vh, got))
+        rp = np.zeros(nq + 1, dtype=np.int64)
+        cols = []
+        for a in range(nq):
+            c = O.kept_tiles_of_row(g, pat, a) if a in tiles else np.zeros(0, np.int32)
+            cols.append(c)
+            rp[a + 1] = rp[a] + len(c)
+        ref = O.sparse_attention_head(qh, kh, vh, rp, np.concatenate(cols), g, q_tiles=tiles)
+        for a in tiles:
+            r0, r1 = a * g.block_m, min(g.N, (a + 1) * g.block_m)
+            assert_attn_close(torch.from_numpy(got[r0:r1]), ref[r0:r1], f"sink, block cover, head {h} tile {a}")
+
+
 @pytest.mark.parametrize("name", ["cogvideox_v1", "hunyuan_skip85"])
 def test_full_size_dense_sampled_rows(name):
     cfg = get_config(name)

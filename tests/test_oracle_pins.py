@@ -192,6 +192,71 @@ def test_layout_hand_worked_example():
     assert O.layout_fwd(x, g)[:, 0].tolist() == [0., 10., 1., 11., 2., 12., 100.]
 
 
+def test_layout_with_first_frame_sink_keeps_frame0_as_a_block():
+    """Hand-worked: F = 3, P = 2, one text token first.  Tokens (f, p): n = 1 + 2 f + p.  With the
+    sink on, the transformed order is text | frame 0 in position order | positions outer over frames
+    1, 2:  (0,0) (0,1) | (1,0) (2,0) (1,1) (2,1)."""
+    g = O.Geometry(1, 1, 3, 2, 1, 1, text_first=1, sink_first_frame=1)
+    #                 text (0,0) (0,1) (1,0) (1,1) (2,0) (2,1)
+    assert O.layout_perm(g).tolist() == [0, 1, 2, 3, 5, 4, 6]
+    x = np.array([[100.], [0.], [1.], [10.], [11.], [20.], [21.]])
+    y = O.layout_fwd(x, g)
+    assert y[:, 0].tolist() == [100., 0., 1., 10., 20., 11., 21.]
+    assert O.layout_inv(y, g)[:, 0].tolist() == x[:, 0].tolist()
+    # without the flag the same geometry interleaves frame 0 with the others
+    g0 = O.Geometry(1, 1, 3, 2, 1, 1, text_first=1, sink_first_frame=0)
+    assert O.layout_fwd(x, g0)[:, 0].tolist() == [100., 0., 10., 20., 1., 11., 21.]
+    # general shapes: a permutation, text fixed, frame 0 = the first P video slots in position order,
+    # the rest = reshape / transpose of frames 1..F-1; F = 1 and P = 1 degenerate to the identity
+    for cfg in (get_config("mid64", sink_first_frame=1), get_config("mid128", sink_first_frame=1)):
+        g = O.Geometry.from_config(cfg)
+        perm = O.layout_perm(g)
+        assert sorted(perm.tolist()) == list(range(g.N))
+        rng = np.random.default_rng(4)
+        x = rng.integers(0, 2 ** 16, size=(g.N, 3), dtype=np.uint16)
+        y = O.layout_fwd(x, g)
+        vid = x[g.off:g.off + g.F * g.P].reshape(g.F, g.P, 3)
+        assert np.array_equal(y[g.off:g.off + g.P], vid[0])
+        assert np.array_equal(y[g.off + g.P:g.off + g.F * g.P], vid[1:].transpose(1, 0, 2).reshape(-1, 3))
+        txt = np.ones(g.N, bool)
+        txt[g.off:g.off + g.F * g.P] = False
+        assert np.array_equal(y[txt], x[txt]) and np.array_equal(O.layout_inv(y, g), x)
+    for F, P in ((1, 7), (7, 1)):
+        g = O.Geometry(1, 1, F, P, 2, 3, sink_first_frame=1)
+        if F == 1:
+            assert O.layout_perm(g).tolist() == list(range(g.N))
+        else:
+            assert sorted(O.layout_perm(g).tolist()) == list(range(g.N))
+
+
+def test_first_frame_sink_costs_a_temporal_head_few_tiles():
+    """The point of the block: with the sink on, a temporal head's query tile keeps the tiles of
+    the frame-0 block and of its window, not every tile (frame 0 spread over every F-th row
+    would touch them all), and the list still covers exactly the element mask."""
+    g = O.Geometry(1, 1, 9, 256, 32, 64, text_first=0, w_s=1, w_t=6, sink_first_frame=1, block_m=128, block_n=64)
+    nq, nk = O.n_tiles(g)
+    rp, ci = O.tile_list(g, O.TEMPORAL)
+    a = nq // 2
+    row = ci[rp[a]:rp[a + 1]]
+    # frame-0 block: 256 rows = 4 tiles; window: (128 / 8 + 2 * 6 + 1) positions * 8 frames ~ 4-5 tiles; text: 1
+    assert 4 + 1 < len(row) <= 4 + 6 + 1 < nk // 2
+    assert set(range(4)) <= set(row.tolist())
+    perm = O.layout_perm(g)
+    inv = np.empty_like(perm)
+    inv[perm] = np.arange(g.N)
+    m = O.temporal_mask(g)[inv][:, inv]
+    for a in range(nq):
+        for b in range(nk):
+            blk = m[a * g.block_m:(a + 1) * g.block_m, b * g.block_n:(b + 1) * g.block_n]
+            assert bool(blk.any()) == (b in ci[rp[a]:rp[a + 1]])
+    # attention through the transformed order equals attention in the original one (Sec. 4.2)
+    rng = np.random.default_rng(8)
+    q, k, v = (rng.normal(0, 1, (g.N, g.D)) for _ in range(3))
+    o_ref = O.masked_attention(q, k, v, O.temporal_mask(g), g.scale)
+    o_p = O.masked_attention(O.layout_fwd(q, g), O.layout_fwd(k, g), O.layout_fwd(v, g), m, g.scale)
+    assert np.allclose(O.layout_inv(o_p, g), o_ref, atol=1e-12)
+
+
 @pytest.mark.parametrize("name", ["tiny", "mid64", "mid128"])
 def test_layout_is_reshape_transpose_and_inverts_bit_exactly(name):
     cfg = get_config(name)
