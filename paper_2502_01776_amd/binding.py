@@ -13,7 +13,8 @@ import numpy as np
 import torch  # noqa: F401  -- must come first: the library binds to the HIP runtime torch has loaded
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libsvg_gfx950.so")
+# SVG_LIBRARY_PATH selects another build of the same library (e.g. to time two builds side by side)
+LIB_PATH = os.environ.get("SVG_LIBRARY_PATH") or os.path.join(_HERE, "libsvg_gfx950.so")
 
 SVG_HEAD_SPATIAL = 0
 SVG_HEAD_TEMPORAL = 1

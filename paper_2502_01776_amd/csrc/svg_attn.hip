@@ -79,12 +79,13 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   constexpr int DB = D / 32;             // 32-row blocks of O^T
   constexpr int K_PIECES = BN * CPR;
   constexpr int V_UNITS = (BN / 8) * CPR;   // a unit = 8 keys x 8 channels
-  // Staging work split: with 4 wavefronts the first V_UNITS threads stage V (8 row
-  // loads + register transpose each) and the others stage K; a single wavefront
-  // does both.
+  // Staging work: with 4 wavefronts every thread stages K_PER_THREAD 16-byte pieces of K and half
+  // a V unit (4 row loads, a register transpose of 4 keys x 8 channels, 8-byte LDS writes), so
+  // that all wavefronts reach the barrier with the same amount of work behind them; a single
+  // wavefront stages whole V units.
   constexpr bool SPLIT = NW == 4;
-  constexpr int K_THREADS = SPLIT ? THREADS - V_UNITS : THREADS;
-  constexpr int K_PER_THREAD = (K_PIECES + K_THREADS - 1) / K_THREADS;
+  constexpr int V_HALVES = 2 * V_UNITS;
+  constexpr int K_PER_THREAD = (K_PIECES + THREADS - 1) / THREADS;
   constexpr int V_PER_THREAD = SPLIT ? 1 : (V_UNITS + THREADS - 1) / THREADS;
   // K staging: row-major, rows padded by 16 bytes so that the 16 lanes served together
   // by a ds_read_b128 of the A operand (16 consecutive keys, same channel piece) fall on
@@ -99,8 +100,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   constexpr int V_ROW = D * 16;
   constexpr int V_BYTES = (BN / 8) * V_ROW;
   constexpr int STAGE_BYTES = K_BYTES + V_BYTES;
-  static_assert(!SPLIT || V_UNITS % 64 == 0, "V staging must be done by whole wavefronts");
-  static_assert(!SPLIT || (V_UNITS < THREADS && K_THREADS % CPR == 0), "K staging threads must cover whole rows");
+  static_assert(!SPLIT || (V_HALVES % 64 == 0 && V_HALVES <= THREADS), "V staging must be done by whole wavefronts");
+  static_assert(!SPLIT || (K_PIECES % THREADS == 0 && THREADS % CPR == 0), "K staging threads must cover whole rows");
 
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE_BYTES];
   __shared__ __attribute__((aligned(16))) int key_code[MASKABLE ? 2 * BN : 4];
@@ -398,14 +399,11 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   // ======================================================================================
   // Staging of one K/V tile.
   // ======================================================================================
-  constexpr int STAGE_REGS = SPLIT ? (K_PER_THREAD > 8 ? K_PER_THREAD : 8) : 1;
-  u32x4 stg[STAGE_REGS];                 // split roles: K pieces or the 8 rows of a V unit
-  u32x4 kst[SPLIT ? 1 : K_PER_THREAD];   // single wavefront: both
-  u32x4 vst[SPLIT ? 1 : V_PER_THREAD][8];
-  // staging role per wavefront: read through readfirstlane so that the compiler treats the
-  // role branch as scalar (otherwise it merges both roles' loads and selects the buffer
-  // descriptor per lane)
-  const bool v_role = SPLIT && __builtin_amdgcn_readfirstlane(tid >> 6) < V_UNITS / 64;
+  u32x4 kst[K_PER_THREAD];               // K pieces
+  u32x4 vst[V_PER_THREAD][SPLIT ? 4 : 8];   // rows of a V unit (four wavefronts: of half a unit)
+  // which wavefronts stage V at all (whole wavefronts; read through readfirstlane so that the
+  // branch is scalar)
+  const bool v_role = !SPLIT || __builtin_amdgcn_readfirstlane(tid >> 6) < V_HALVES / 64;
 
   // row of the e-th key of V group kg8 = (kb, kk, g):  32 kb + 16 kk + 4 g + e (+4 if e >= 4)
   auto v_key = [](int kg8, int e) { return (kg8 >> 1) * 16 + (kg8 & 1) * 4 + e + (e >= 4 ? 4 : 0); };
@@ -413,11 +411,10 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   // The descriptor of a tile starts at the tile's first key row and covers the rows up to
   // N, so the per-thread offsets are loop invariant, no clamping arithmetic is needed, and
   // rows beyond N (ragged last tile) read as zero.
-  int stage_off = 0;
-  if (SPLIT) {
-    if (v_role) stage_off = (v_key(tid / CPR, 0) * D + (tid % CPR) * 8) * 2;
-    else stage_off = (((tid - V_UNITS) / CPR) * D + ((tid - V_UNITS) % CPR) * 8) * 2;
-  }
+  // four wavefronts: thread tid stages the K pieces tid + i * THREADS, and keys 4 h .. 4 h + 3 of the
+  // V unit tid / 2 with h = tid % 2 (the two threads of a unit write the two halves of its slots)
+  const int k_stage_off = SPLIT ? ((tid / CPR) * D + (tid % CPR) * 8) * 2 : 0;
+  const int v_stage_off = SPLIT ? (v_key((tid >> 1) / CPR, 4 * (tid & 1)) * D + ((tid >> 1) % CPR) * 8) * 2 : 0;
 
   auto load_tile = [&](int col_any) {
     // the tile index is the same in every lane; saying so keeps the descriptors scalar
@@ -428,15 +425,13 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<__bf16*>(vh + (size_t)key0 * D), 0, bytes_left, kRsrcFlags);
     if (SPLIT) {
+#pragma unroll
+      for (int i = 0; i < K_PER_THREAD; ++i)    // piece tid + i * THREADS: THREADS / CPR rows further on
+        kst[i] = __builtin_amdgcn_raw_buffer_load_b128(rk, k_stage_off + i * (THREADS / CPR) * (D * 2), 0, 0);
       if (v_role) {
 #pragma unroll
-        for (int e = 0; e < 8; ++e)   // rows +0..3 and +8..11 of the group's first row
-          stg[e] = __builtin_amdgcn_raw_buffer_load_b128(rv, stage_off + (e + (e >= 4 ? 4 : 0)) * (D * 2), 0, 0);
-      } else {
-#pragma unroll
-        for (int i = 0; i < K_PER_THREAD; ++i)    // piece (tid - V_UNITS) + i * K_THREADS
-          if (K_PIECES % K_THREADS == 0 || (tid - V_UNITS) + i * K_THREADS < K_PIECES)
-            stg[i] = __builtin_amdgcn_raw_buffer_load_b128(rk, stage_off + i * (K_THREADS / CPR) * (D * 2), 0, 0);
+        for (int e = 0; e < 4; ++e)              // four consecutive rows
+          vst[0][e] = __builtin_amdgcn_raw_buffer_load_b128(rv, v_stage_off + e * (D * 2), 0, 0);
       }
     } else {
 #pragma unroll
@@ -471,20 +466,30 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     }
   };
 
+  // 4 keys x 8 channels -> the 8-byte half h of the unit's eight 16-byte slots
+  auto store_v_half = [&](unsigned char* vb, int kg8, int c, int h, const u32x4* rows) {
+    unsigned char* dst = vb + kg8 * V_ROW + c * 128 + h * 8;
+    const int sw = c & 7;
+#pragma unroll
+    for (int dd = 0; dd < 8; ++dd) {
+      const unsigned sel = (dd & 1) ? 0x07060302u : 0x05040100u;
+      u32x2 o;
+      o[0] = __builtin_amdgcn_perm(rows[1][dd >> 1], rows[0][dd >> 1], sel);
+      o[1] = __builtin_amdgcn_perm(rows[3][dd >> 1], rows[2][dd >> 1], sel);
+      *reinterpret_cast<u32x2*>(dst + ((dd ^ sw) << 4)) = o;
+    }
+  };
+
   auto store_tile = [&](int buf, int col) {
     unsigned char* kb = lds + buf * STAGE_BYTES;
     unsigned char* vb = kb + K_BYTES;
     if (SPLIT) {
-      if (v_role) {
-        store_v_unit(vb, tid / CPR, tid % CPR, stg);
-      } else {
 #pragma unroll
-        for (int i = 0; i < K_PER_THREAD; ++i) {
-          const int u = (tid - V_UNITS) + i * K_THREADS;
-          if (K_PIECES % K_THREADS == 0 || u < K_PIECES)
-            *reinterpret_cast<u32x4*>(kb + (u / CPR) * K_ROW + ((u % CPR) << 4)) = stg[i];
-        }
+      for (int i = 0; i < K_PER_THREAD; ++i) {
+        const int u = tid + i * THREADS;
+        *reinterpret_cast<u32x4*>(kb + (u / CPR) * K_ROW + ((u % CPR) << 4)) = kst[i];
       }
+      if (v_role) store_v_half(vb, (tid >> 1) / CPR, (tid >> 1) % CPR, tid & 1, vst[0]);
     } else {
 #pragma unroll
       for (int i = 0; i < K_PER_THREAD; ++i) {
