@@ -29,7 +29,7 @@
 // looking at the tile's own maximum; only when a row sum shows that the reference is
 // too small does the wave fall back to the classic update (tile maximum, rescale).
 // P is rounded to bf16 for the second product; accumulation is fp32; the running sum
-// uses the unrounded P.
+// uses the unrounded P at head dimension 128 and the rounded P at head dimension 64.
 //
 // Measured on MI355X:
 //  * With 32 query rows per wavefront every MFMA needs a fresh 1 KB operand from LDS,
@@ -171,10 +171,16 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   int qslot = grp * BM + wave * 32 + r;     // row (profile: index into rows[])
   int qrow;
   if (MODE == kProfile) {
+    // The sampled rows are dealt evenly to the row groups (rows_per_group each, so that no
+    // group is left with a handful of rows and idle wavefronts); a lane without a row of
+    // its own shadows the group's first row and writes nothing.
+    const int in_group = wave * 32 + r;
+    const int first = min(grp * a.rows_per_group, a.t - 1);
+    qslot = in_group < a.rows_per_group ? grp * a.rows_per_group + in_group : a.t;
     // The temporal variant takes the sampled rows grouped by in-frame position, so that
     // a workgroup's rows share a narrow position range and most key tiles can be
     // skipped; results are still written at the row's own slot.
-    int slot = min(qslot, a.t - 1);
+    int slot = qslot < a.t ? qslot : first;
     if (variant == 2) slot = a.order_t[slot];
     if (qslot < a.t) qslot = slot;
     qrow = a.rows[slot];
@@ -274,6 +280,11 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     if (lleft > 1) {
       const int first_video_tile = (a.off + BN - 1) / BN;      // tiles before it are text-prefix tiles
       auto holds_text = [&](int gq) { return gq * BM < a.off || (gq + 1) * BM > a.video_end; };
+      // own first and last entry: a list is one run of consecutive tiles (the window) with the
+      // text tiles in front of or behind it, so the place of a tile inside it can usually be
+      // told from one of its ends without searching (every load saved here is a memory
+      // round trip in front of a workgroup whose whole list may be a few dozen tiles long)
+      const int c_first = cols[lbeg], c_last = cols[lend - 1];
       // cohort: the logical ids of the same aligned block of cs, as far as they belong to this
       // head; u = position of a query tile in the head's dispatch order
       for (int cs = kCohort; cs >= 16; cs >>= 2) {
@@ -284,11 +295,23 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
         const int bottom = a.reverse_q ? a.nqt - 1 - u1 : u0;
         while (top > bottom && holds_text(top)) --top;
         if (holds_text(top)) break;
+        // its first entry that is no text-prefix tile, among the first eight (loaded together)
+        const int tb = rp[top], te = rp[top + 1];
+        int cand[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) cand[j] = cols[min(tb + j, te - 1)];
         int anchor = -1;
-        for (int j = rp[top], e = min(rp[top + 1], rp[top] + 8); j < e; ++j)
-          if (cols[j] >= first_video_tile) { anchor = cols[j]; break; }
+#pragma unroll
+        for (int j = 7; j >= 0; --j)
+          if (tb + j < te && cand[j] >= first_video_tile) anchor = cand[j];
         if (anchor < 0) break;
-        // first own entry >= anchor (binary search); usable if the anchor lies inside the own list
+        // own entry == anchor: counted from the front, from the back, else by binary search
+        const int from_front = anchor - c_first, from_back = (lleft - 1) - (c_last - anchor);
+        const bool front_ok = from_front >= 0 && from_front < lleft, back_ok = from_back >= 0 && from_back < lleft;
+        const int at_front = cols[lbeg + (front_ok ? from_front : 0)];
+        const int at_back = cols[lbeg + (back_ok ? from_back : 0)];
+        if (front_ok && at_front == anchor) { lj = lbeg + from_front; break; }
+        if (back_ok && at_back == anchor) { lj = lbeg + from_back; break; }
         int lo = 0, hi = lleft;
         while (lo < hi) {
           const int mid = (lo + hi) >> 1;
@@ -624,7 +647,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
       // ---- S^T = K Q^T.  Operand reads run PF products ahead of their use (a rolling
       // window of PF operand registers), so after the first few the LDS latency is hidden
       // behind the MFMAs; the scheduling barriers pin the read / product interleave.
-      constexpr int PF = (MASKABLE || BN == 128) ? 2 : kPrefetch;   // (those forms are short of registers)
+      constexpr int PF = MASKABLE ? 2 : kPrefetch;   // (the masked forms are short of registers)
       constexpr int NS = KB * DS;          // operands of the first product, order (kb, s)
       constexpr int NV = KB * 2 * DB;      // operands of the second product, order (kb, kk, db)
       auto k_operand = [&](int i) -> bf16x8 {
@@ -717,9 +740,23 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
               p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sacc[kb][8 * kk + e], a.scale_log2, -mc));
-              l_loc += p[e];
+              if (D != 64) l_loc += p[e];
             }
             pb[kb][kk] = __builtin_convertvector(p, bf16x8);
+            if (D == 64) {
+              // Head dimension 64 is bound by the softmax's VALU work, so the row sum is taken two
+              // weights per instruction: dot products of the packed pairs with (1, 1), i.e. over
+              // the ROUNDED weights.  (At D = 128 this was slower: the dot products run on the
+              // matrix pipeline and compete with the MFMAs there.)  The pairs are taken by vector
+              // shuffles: extracted as 32-bit words of the bit-cast vector, the compiler fed all
+              // four dot products the same register.
+              const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+              const bf16x8 pv = pb[kb][kk];
+              l_loc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pv, pv, 0, 1), ones, l_loc, false);
+              l_loc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pv, pv, 2, 3), ones, l_loc, false);
+              l_loc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pv, pv, 4, 5), ones, l_loc, false);
+              l_loc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_shufflevector(pv, pv, 6, 7), ones, l_loc, false);
+            }
           }
         return l_loc;
       };
@@ -1000,6 +1037,8 @@ int launch_profile(const Geo& g, const void* q, const void* k, const void* v, co
   // [BH][ceil(t/16)], row order int32 [t]
   const int ns = profile_splits(g);
   a.nsplit = ns;
+  const int groups = (t + g.bm - 1) / g.bm;
+  a.rows_per_group = (t + groups - 1) / groups;
   const size_t out_floats = (size_t)(ns + 2) * a.BH * t * g.D;
   float2* stats = reinterpret_cast<float2*>(workspace + out_floats);
   const int n_partial = (t + kErrRows - 1) / kErrRows;

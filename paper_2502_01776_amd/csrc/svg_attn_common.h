@@ -7,6 +7,7 @@ namespace attn {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -35,6 +36,7 @@ struct AttnArgs {
   const int32_t* order_t;     // profile: indices into rows[], grouped by in-frame position (temporal variant)
   int t;                      // profile: number of sampled rows
   int nsplit;                 // profile: key ranges the unmasked pass is cut into
+  int rows_per_group;         // profile: sampled rows per workgroup (the groups are balanced)
   float2* stats;              // profile: (reference maximum, row sum) per (key range, head, row)
   int N, nk, BH;
   int nqt;                    // workgroups per head: query tiles (dense, sparse) or ceil(t / rows per workgroup) (profile)
