@@ -185,20 +185,25 @@ def cpu_baseline(cfg, q, k, v, rows, labels_np, nnz_total, o_bf16=None, o_fp8=No
 def measured_matrix_peak(S, torch, ms_target=12.0):
     """Sustained rate of the bf16 matrix cores on this machine: a loop of products only (form 0) and
     the same loop with the per-product LDS read and softmax instructions of the D = 128 attention
-    kernel (form 1), on normally distributed operands, each timed over >= 10 ms."""
+    kernel (form 1), on normally distributed operands, each timed over >= 10 ms; and the
+    product-only loop on all-zero operands, which shows how much of the published peak is lost to
+    the power the data toggling draws (the clock drops under real data, not under zeros)."""
     gen = torch.Generator(device="cuda").manual_seed(11)
     operands = torch.randn(1 << 19, generator=gen, device="cuda").to(torch.bfloat16)      # 1 MiB
     wgs = 2048
     sink = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
     out = {}
-    for form, key in ((0, "products_only"), (1, "with_lds_operand_reads_and_softmax_instructions")):
+    zeros = torch.zeros_like(operands)
+    for form, key, ops in ((0, "products_only", operands),
+                           (1, "with_lds_operand_reads_and_softmax_instructions", operands),
+                           (0, "products_only_constant_operands", zeros)):
         iters = 500
         for attempt in range(3):
-            S.svg_probe_mfma_bf16(form, wgs, iters, operands, sink)          # warm-up / calibration
+            S.svg_probe_mfma_bf16(form, wgs, iters, ops, sink)          # warm-up / calibration
             torch.cuda.synchronize()
             e0, e1 = ev(), ev()
             e0.record()
-            flop = S.svg_probe_mfma_bf16(form, wgs, iters, operands, sink)
+            flop = S.svg_probe_mfma_bf16(form, wgs, iters, ops, sink)
             e1.record()
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1)
@@ -396,6 +401,7 @@ def main():
         out["roofline"]["frac_of_measured_peak"] = achieved / mp
         out["roofline"]["measured_peak_with_kernel_instruction_mix"] = mix
         out["roofline"]["frac_of_instruction_mix_bound"] = achieved / mix
+        out["roofline"]["measured_peak_constant_operands"] = peak_live["products_only_constant_operands"]["tflops"]
         out["roofline"]["measured_peak_detail"] = peak_live
     o8_keep = None
     if not args.no_fp8 and S.svg_fp8_buffer_bytes(sh, S.SVG_FP8_Q) > 0:

@@ -647,7 +647,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
       // ---- S^T = K Q^T.  Operand reads run PF products ahead of their use (a rolling
       // window of PF operand registers), so after the first few the LDS latency is hidden
       // behind the MFMAs; the scheduling barriers pin the read / product interleave.
-      constexpr int PF = MASKABLE ? 2 : kPrefetch;   // (the masked forms are short of registers)
+      constexpr int PF = kPrefetch;
       constexpr int NS = KB * DS;          // operands of the first product, order (kb, s)
       constexpr int NV = KB * 2 * DB;      // operands of the second product, order (kb, kk, db)
       auto k_operand = [&](int i) -> bf16x8 {
