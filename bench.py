@@ -41,6 +41,9 @@ def parse():
     ap.add_argument("--profile-percent", type=float, default=None,
                     help="percentage of the query rows that online profiling samples (default: the workload's "
                          "1 %%; the paper's ablation uses 0.1, 1, 5 and 100)")
+    ap.add_argument("--profile-sweep", action="store_true",
+                    help="also time the profiling stage alone at 0.1, 1, 5 and 100 %% of the query rows (the paper's "
+                         "Table 3 ratios) and report it as 'profile_ratio_sweep' beside the dense time")
     ap.add_argument("--without-layout-transform", action="store_true",
                     help="also time the comparison arm of Sec. 5.5: temporal heads left in frame-major order "
                          "with the frame-major temporal tile list (no layout kernels)")
@@ -511,6 +514,35 @@ def main():
             "roofline": {"kernel": "norm_rope_kernel<%d>" % D, "bound": "hbm", "achieved": moved / (ms_fused * 1e-3) / 1e9,
                          "peak": PEAK_HBM_GBS, "unit": "GB/s", "frac": moved / (ms_fused * 1e-3) / 1e9 / PEAK_HBM_GBS},
         }
+    if args.profile_sweep:
+        # the stage alone, at the sampling ratios of the paper's ablation; labels must not depend on the ratio
+        # for planted heads, so they are reported too
+        sweep = []
+        for pct in (0.1, 1.0, 5.0, 100.0):
+            rows_p = sample_rows(cfg, t=max(1, min(N, int(np.ceil(N * pct / 100.0)))))
+            tp = len(rows_p)
+            rows_d = torch.from_numpy(rows_p).cuda()
+            nb = S.svg_workspace_bytes(sh, tp)
+            wsp = torch.empty(nb, dtype=torch.uint8, device="cuda")
+            lab_p = torch.zeros(BH, dtype=torch.uint8, device="cuda")
+            reps = 2 if pct > 50 else max(3, args.steps)
+            S.svg_profile_heads(sh, q, k, v, rows_d, tp, lab_p, mse, wsp, nb)
+            torch.cuda.synchronize()
+            times = []
+            for _ in range(reps):
+                e0, e1 = ev(), ev()
+                e0.record()
+                S.svg_profile_heads(sh, q, k, v, rows_d, tp, lab_p, mse, wsp, nb)
+                e1.record()
+                torch.cuda.synchronize()
+                times.append(e0.elapsed_time(e1))
+            ms_p = float(np.median(times))
+            sweep.append({"percent_of_rows": pct, "rows": tp, "profile_ms": ms_p,
+                          "fraction_of_dense_attention": None if dense_ms is None else ms_p / dense_ms,
+                          "labels_equal_to_the_1_percent_run": bool((lab_p.cpu().numpy() == labels_np).all()),
+                          "workspace_mb": nb / 1e6})
+            del wsp
+        out["profile_ratio_sweep"] = sweep
     if args.without_layout_transform:
         # same labels, same kernel, unpermuted q, k, v: the temporal slot gets the list of the
         # temporal mask in frame-major order
