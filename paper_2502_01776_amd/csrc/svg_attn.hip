@@ -33,17 +33,22 @@
 //
 // Measured on MI355X:
 //  * With 32 query rows per wavefront every MFMA needs a fresh 1 KB operand from LDS,
-//    which by itself saturates the 128 B/clk LDS port at MFMA peak; together with the
-//    staging writes the LDS is busy about 70 % of the time at the speed reached here.
+//    which by itself saturates the 128 B/clk LDS data path at MFMA peak; together with the
+//    staging writes that path is busy about 80 % of the time at the speed reached here.
+//  * The chip is power-limited under this load: the shader clock sits near 1.7 GHz (2.4 GHz
+//    nominal), and a loop of nothing but MFMAs on random operands is held there too.  A
+//    variant that idles more runs at a higher clock and ends up at the same rate; what
+//    pays is less work per tile (instructions, LDS and memory traffic), not fewer cycles.
 //  * A lone wavefront hides only about 12 cycles of other instructions behind each
 //    32-cycle MFMA; two wavefronts on a SIMD overlap one's VALU work with the other's
 //    products much better, and best when each runs long homogeneous phases (products /
 //    softmax) and the one issuing products has the higher wave priority.  Interleaving
 //    softmax slices between the products of the same wavefront was 10 % slower.
-//  * A 64-row-per-wavefront variant (O^T and Q^T in accumulation registers through
-//    hand-written MFMA statements, one wavefront per SIMD, software pipelined) halves the
-//    LDS reads but loses that overlap and came out 8 % slower; an 8-wavefront,
-//    two-query-tile workgroup was slower as well.
+//  * 64 query rows per wavefront (every LDS operand feeding two products) needs more than
+//    the 256 registers a wavefront has at two per SIMD; with one wavefront per SIMD it
+//    loses the overlap above and was 5 % slower.  A 256-row workgroup (two query tiles
+//    sharing every staged tile, the two halves one phase apart) halved staging and L2
+//    traffic per product and came out even: more cycles at a higher clock.
 #include "svg_attn_common.h"
 
 namespace svg {
