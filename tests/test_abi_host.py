@@ -273,6 +273,17 @@ def test_fp8_buffer_sizes_and_argument_checks_without_gpu():
     assert lib.svg_fp8_quantize(C.byref(sh), p[5], p[6], p[7], None, p[0], p[1], p[2], p[2] + 16, None) == -4
 
 
+def test_rate_probe_argument_checks_without_gpu():
+    lib = S.lib()
+    a = 0x10000000
+    flop = C.c_double()
+    assert lib.svg_probe_mfma_bf16(2, 8, 1, a, a, C.byref(flop), None) == -1        # unknown form
+    assert lib.svg_probe_mfma_bf16(0, 0, 1, a, a, C.byref(flop), None) == -1
+    assert lib.svg_probe_mfma_bf16(0, 8, 0, a, a, C.byref(flop), None) == -1
+    assert lib.svg_probe_mfma_bf16(0, 8, 1, None, a, C.byref(flop), None) == -1
+    assert lib.svg_probe_mfma_bf16(1, 8, 1, a + 2, a, C.byref(flop), None) == -1
+
+
 def test_qk_norm_rope_argument_checks_without_gpu():
     lib = S.lib()
     sh = S.shape_from_config(get_config("mid64"))

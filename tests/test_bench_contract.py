@@ -34,3 +34,19 @@ def test_json_line_has_the_contract_fields():
     assert cb["kind"] == "oracle" and cb["cores"] >= 1 and cb["value"] > 0 and cb["sample"]
     assert d["value"] > 0 and abs(d["ms_per_step"] - d["ms_per_layer"]) < 1e-9
     assert d["fp8"]["roofline"]["peak"] == 5000.0 and d["qk_norm_rope"]["roofline"]["bound"] == "hbm"
+    # measured ceilings of the same box, live: zeros > random operands > with the kernel's instruction mix > the kernel
+    assert rf["measured_peak_constant_operands"] > rf["measured_peak"] > rf["measured_peak_with_kernel_instruction_mix"] > rf["achieved"]
+    assert cb["host_cpus"] >= 1 and cb["cores"] >= 1 and rf["traffic_live"] in (False, None)
+
+
+@pytest.mark.gpu
+def test_matrix_core_rate_probe_runs_and_counts_its_work():
+    import torch
+    import paper_2502_01776_amd as S
+    ops = torch.randn(1 << 19, device="cuda").to(torch.bfloat16)
+    sink = torch.zeros(64 * 256, dtype=torch.float32, device="cuda")
+    for form in (0, 1):
+        flop = S.svg_probe_mfma_bf16(form, 64, 10, ops, sink)
+        torch.cuda.synchronize()
+        assert flop == 64 * 4 * 10 * 16 * 2.0 * 32 * 32 * 16
+        assert torch.isfinite(sink).all()
