@@ -58,7 +58,7 @@ __global__ __launch_bounds__(kProbeThreads, 2) void probe_kernel(const u32x4* da
       __builtin_amdgcn_sched_barrier(0);
       if (FORM == 1) {
         f[m & 7] = __builtin_fmaf(f[m & 7], 0.999f, 1e-3f);
-        f[(m + 1) & 7] = __builtin_amdgcn_exp2f(f[(m + 1) & 7]);
+        f[(m + 1) & 7] = __builtin_amdgcn_exp2f(-f[(m + 1) & 7]);      // (negated: the chain stays finite)
         f[(m + 2) & 7] += f[(m + 3) & 7];
         if (m & 1) {
           const f32x2 two = {f[m & 7], f[(m + 1) & 7]};
