@@ -121,7 +121,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   // stream the same K/V share one L2.
   // ======================================================================================
   const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
-  int bh, grp, variant = 0, chunk = 0, lid = 0;
+  int bh = 0, grp = 0, variant = 0, chunk = 0;
   if (MODE == kProfile) {
     // (head, row group) pairs are split into 8 contiguous chunks, one per XCD.  Each pair
     // has nsplit + 2 units of similar length: the unmasked pass cut into nsplit key
@@ -139,23 +139,26 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     chunk = unit < 2 ? 0 : unit - 2;
     bh = pair / a.nqt;
     grp = pair - bh * a.nqt;
-  } else {
-    if (MODE == kDense) {
-      // Dense: blocks of kCohort consecutive logical ids go to one XCD, consecutive blocks to
-      // consecutive XCDs.  An XCD's L2 serves neighbouring query tiles of one head, and at
-      // any time all XCDs work on the same one or two heads, whose K/V (61 MB per head at
-      // the 120k-token shape) then stay in the memory-side cache in front of HBM; with one
-      // head per XCD the dense pass runs into the HBM bandwidth (-11 % time).
-      lid = ((loc / kCohort) * 8 + xcd) * kCohort + (loc % kCohort);
-    } else {
-      // Sparse: one contiguous chunk of logical ids per XCD, so that consecutive cohorts,
-      // whose key windows overlap, find each other's K/V tiles in the same L2.
-      lid = xcd * ((a.total + 7) >> 3) + loc;
-    }
+  } else if (MODE == kDense) {
+    // Dense: blocks of kCohort consecutive logical ids go to one XCD, consecutive blocks to
+    // consecutive XCDs.  An XCD's L2 serves neighbouring query tiles of one head, and at
+    // any time all XCDs work on the same one or two heads, whose K/V (61 MB per head at
+    // the 120k-token shape) then stay in the memory-side cache in front of HBM; with one
+    // head per XCD the dense pass runs into the HBM bandwidth (-11 % time).
+    const int lid = ((loc / kCohort) * 8 + xcd) * kCohort + (loc % kCohort);
     if (lid >= a.total) return;
     bh = lid / a.nqt;
     grp = lid - bh * a.nqt;
-    if (a.reverse_q) grp = a.nqt - 1 - grp;
+  }
+  // sparse: heavy tiles first, then an eighth of each label's sequence of tiles
+  int pat = 0, cl = -1, head_cl0 = 0;
+  if (SPARSE) {
+    if (!sparse_slot(a.so, a.BH, a.labels, a.row_ptr[0], a.row_ptr[1], bh, grp, pat, cl, head_cl0)) return;
+    bh = __builtin_amdgcn_readfirstlane(bh);
+    grp = __builtin_amdgcn_readfirstlane(grp);
+    pat = __builtin_amdgcn_readfirstlane(pat);
+    cl = __builtin_amdgcn_readfirstlane(cl);
+    head_cl0 = __builtin_amdgcn_readfirstlane(head_cl0);
   }
 
   // profile: the unmasked pass needs no key codes, tile summaries or element masks (only the
@@ -222,7 +225,6 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   // head that this lane reads and writes is the token whose transformed position is qrow
   // (Sec. 4.2: position off + p F + f holds token off + f P + p; with the first-frame sink,
   // frame 0 leads as a block)
-  const int pat = SPARSE && a.labels ? (a.labels[bh] != 0) : 0;
   // a temporal head reads the P-outer copies of k and v when the caller keeps them apart from
   // the originals (which the spatial heads read in place)
   const bool kv_copy = SPARSE && __builtin_amdgcn_readfirstlane(pat) != 0 && a.k_t != nullptr;
@@ -282,24 +284,19 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     // as they run at the same pace they all want the same K/V tile at the same time.  The
     // order of the tiles does not change the result beyond fp32 summation order, and a
     // full list (every member starts at tile 0) is walked exactly like the dense kernel.
-    if (lleft > 1) {
+    if (lleft > 1 && cl >= 0) {
       const int first_video_tile = (a.off + BN - 1) / BN;      // tiles before it are text-prefix tiles
-      auto holds_text = [&](int gq) { return gq * BM < a.off || (gq + 1) * BM > a.video_end; };
       // own first and last entry: a list is one run of consecutive tiles (the window) with the
       // text tiles in front of or behind it, so the place of a tile inside it can usually be
       // told from one of its ends without searching (every load saved here is a memory
       // round trip in front of a workgroup whose whole list may be a few dozen tiles long)
       const int c_first = cols[lbeg], c_last = cols[lend - 1];
-      // cohort: the logical ids of the same aligned block of cs, as far as they belong to this
-      // head; u = position of a query tile in the head's dispatch order
+      // cohort: the tiles of the same aligned block of cs in the label's sequence, as far as they
+      // belong to this head (none of them holds a text row; a tile that does starts at the
+      // beginning of its list, which is every key tile)
       for (int cs = kCohort; cs >= 16; cs >>= 2) {
-        const int u0 = max(lid & ~(cs - 1), bh * a.nqt) - bh * a.nqt;
-        const int u1 = min(lid | (cs - 1), (bh + 1) * a.nqt - 1) - bh * a.nqt;
-        // member with the highest window: highest query tile of the cohort that holds no text row
-        int top = a.reverse_q ? a.nqt - 1 - u0 : u1;
-        const int bottom = a.reverse_q ? a.nqt - 1 - u1 : u0;
-        while (top > bottom && holds_text(top)) --top;
-        if (holds_text(top)) break;
+        // member with the highest window: the last query tile of the cohort
+        const int top = a.so.g_lo + min(cl | (cs - 1), head_cl0 + a.so.nl - 1) - head_cl0;
         // its first entry that is no text-prefix tile, among the first eight (loaded together)
         const int tb = rp[top], te = rp[top + 1];
         int cand[8];
@@ -979,9 +976,10 @@ int launch_one(AttnArgs a, int rows_total, hipStream_t stream) {
   constexpr int BM = 32 * NW;
   a.nqt = (rows_total + BM - 1) / BM;
   a.total = a.BH * a.nqt;
-  const unsigned per_xcd = MODE == kDense ? (unsigned)((a.total + 8 * kCohort - 1) / (8 * kCohort)) * kCohort
-                                          : (unsigned)((a.total + 7) / 8);
-  const unsigned grid = MODE == kProfile ? (unsigned)(8 * (a.nsplit + 2) * ((a.total + 7) / 8)) : 8u * per_xcd;
+  const unsigned per_xcd = (unsigned)((a.total + 8 * kCohort - 1) / (8 * kCohort)) * kCohort;   // dense
+  if (MODE == kSparse || MODE == kSparseExact) a.so = sparse_order(a.BH, a.nqt, BM, a.off, a.video_end, a.N);
+  const unsigned grid = MODE == kProfile ? (unsigned)(8 * (a.nsplit + 2) * ((a.total + 7) / 8))
+                        : MODE == kDense ? 8u * per_xcd : sparse_grid(a.so, a.BH);
   (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
   hipLaunchKernelGGL((attn_kernel<D, NW, BN, MODE>), dim3(grid), dim3(64 * NW), 0, stream, a);
   return hip_status(hipGetLastError());
@@ -1026,8 +1024,6 @@ int launch_attention(const Geo& g, const void* q, const void* k, const void* v, 
   a.qo_token_order = sparse && qo_token_order ? 1 : 0;
   a.row_ptr[0] = row_ptr_s; a.col_idx[0] = col_idx_s;
   a.row_ptr[1] = row_ptr_t; a.col_idx[1] = col_idx_t;
-  // query tiles holding text rows keep every key tile: start them first
-  a.reverse_q = (sparse && g.T > 0 && !g.text_first) ? 1 : 0;
   if (sparse && element_mask) return dispatch<kSparseExact>(g, a, g.N, stream);
   return sparse ? dispatch<kSparse>(g, a, g.N, stream) : dispatch<kDense>(g, a, g.N, stream);
 }

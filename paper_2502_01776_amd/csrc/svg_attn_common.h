@@ -22,6 +22,109 @@ constexpr int kCodeKeep = 0x7ffffffe;   // text key / sink key: kept by every qu
 constexpr float kNegBig = -1.0e30f;     // finite stand-in for -inf as the initial row maximum
 constexpr float kLazySum = 8192.0f;      // a lane's per-tile sum of exponentials above this forces a new reference maximum
 
+// --------------------------------------------------------------------------------------------
+// Dispatch order of the block-sparse passes.
+//
+// Workgroups are dealt round-robin to the 8 XCDs (blockIdx.x % 8) and start in the order of
+// blockIdx.x / 8, so what a workgroup works on decides both which L2 serves it and when it
+// starts.  Two things make query tiles unequal: a tile that holds a text row keeps every key
+// tile (its list is many times longer than the others'), and the lists of the two patterns
+// differ in length while the labels, known on the device only, say which heads have which.
+//  * Heavy tiles (those with a text row) start first on every XCD, a head's heavy tiles on
+//    one XCD (they stream the same K and V), heads dealt to the XCDs in turn.  Started last
+//    they would run on alone after every other workgroup of their XCD has finished.
+//  * The other tiles of all heads with the same label form one sequence (head after head,
+//    ascending query tiles); every XCD takes one contiguous eighth of the spatial sequence
+//    and one of the temporal sequence, the one with the longer lists first.  Each XCD so gets
+//    the same share of both kinds of work whatever the labels are, and consecutive workgroups
+//    of an XCD still are neighbouring query tiles of one head (overlapping key windows).
+// With more than 64 heads the labels are not looked at: one sequence in head order.
+// --------------------------------------------------------------------------------------------
+struct SparseOrder {
+  int g_lo;    // a head's query tiles without a text row are [g_lo, g_lo + nl)
+  int nl;
+  int nh;      // tiles with a text row per head (the others, ascending)
+  int hmax;    // workgroups per XCD reserved for them
+};
+
+inline SparseOrder sparse_order(int BH, int nqt, int BM, int off, int video_end, int N) {
+  SparseOrder so;
+  const int lo = off > 0 ? (off + BM - 1) / BM : 0;
+  int hi = video_end < N ? video_end / BM : nqt;
+  so.g_lo = lo < nqt ? lo : nqt;
+  if (hi < so.g_lo) hi = so.g_lo;
+  so.nl = hi - so.g_lo;
+  so.nh = nqt - so.nl;
+  so.hmax = so.nh * ((BH + 7) / 8);
+  return so;
+}
+
+// grid size: an XCD's two eighths together hold at most floor(BH nl / 8) + 2 tiles
+inline unsigned sparse_grid(const SparseOrder& so, int BH) {
+  return 8u * (unsigned)(so.hmax + (long long)BH * so.nl / 8 + 2);
+}
+
+// Which (head, query tile, pattern) does this workgroup take?  false: none.  For a tile without
+// text rows, cl is its index in its label's sequence and head_cl0 the index of its head's first
+// tile there (cl = -1 for a heavy tile).  Every value returned is the same in all lanes.
+__device__ __forceinline__ bool sparse_slot(const SparseOrder so, const int BH, const uint8_t* labels,
+                                            const int32_t* rp_s, const int32_t* rp_t, int& bh, int& grp,
+                                            int& pat, int& cl, int& head_cl0) {
+  const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
+  const int lane = threadIdx.x & 63;
+  const bool classed = labels != nullptr && BH <= 64;
+  unsigned long long m = 0;       // bit h: head h is temporal
+  if (classed) m = __builtin_amdgcn_ballot_w64(lane < BH && labels[lane < BH ? lane : 0] != 0);
+  cl = -1;
+  head_cl0 = 0;
+  if (loc < so.hmax) {
+    const int hh = loc / so.nh, j = loc - hh * so.nh;
+    bh = xcd + 8 * hh;
+    if (bh >= BH) return false;
+    grp = j < so.g_lo ? j : j + so.nl;
+    pat = classed ? (int)((m >> bh) & 1) : (labels ? labels[bh] != 0 : 0);
+    return true;
+  }
+  if (so.nl == 0) return false;
+  int l = loc - so.hmax;
+  const int nT = __builtin_popcountll(m), nS = BH - nT;
+  int first = nS == 0;            // the label whose sequence comes first
+  if (nT > 0 && nS > 0) {
+    const int nnz_s = rp_s[so.g_lo + so.nl] - rp_s[so.g_lo];
+    const int nnz_t = rp_t[so.g_lo + so.nl] - rp_t[so.g_lo];
+    first = nnz_t > nnz_s;
+  }
+  const int nA = first ? nT : nS;
+  const long long NA = (long long)nA * so.nl, NB = (long long)(BH - nA) * so.nl;
+  const int a0 = (int)((xcd * NA) >> 3), a1 = (int)(((xcd + 1) * NA) >> 3);
+  const int b0 = (int)((xcd * NB) >> 3), b1 = (int)(((xcd + 1) * NB) >> 3);
+  int c = first;
+  if (l < a1 - a0) {
+    cl = a0 + l;
+  } else {
+    l -= a1 - a0;
+    if (l >= b1 - b0) return false;
+    cl = b0 + l;
+    c = !first;
+  }
+  const int kth = cl / so.nl;
+  head_cl0 = kth * so.nl;
+  grp = so.g_lo + (cl - head_cl0);
+  if (classed) {
+    // the kth head (from 0) with label c
+    const unsigned long long valid = BH == 64 ? ~0ull : (1ull << BH) - 1;
+    const unsigned long long cm = c ? m : ~m & valid;
+    const int rank = __builtin_popcountll(cm & ((1ull << lane) - 1));
+    const unsigned long long hit = __builtin_amdgcn_ballot_w64(((cm >> lane) & 1) != 0 && rank == kth);
+    bh = __builtin_ctzll(hit);
+    pat = c;
+  } else {
+    bh = kth;
+    pat = labels ? labels[bh] != 0 : 0;
+  }
+  return true;
+}
+
 struct AttnArgs {
   const __bf16* q;
   const __bf16* k;
@@ -40,7 +143,7 @@ struct AttnArgs {
   float2* stats;              // profile: (reference maximum, row sum) per (key range, head, row)
   int N, nk, BH;
   int nqt;                    // workgroups per head: query tiles (dense, sparse) or ceil(t / rows per workgroup) (profile)
-  int reverse_q;              // process query tiles last-to-first (heavy text-suffix tiles first)
+  SparseOrder so;             // sparse: which workgroup takes which (head, query tile)
   int total;                  // logical workgroups
   int qo_token_order;         // sparse: q is read and o written in token order also for temporal heads
   float scale_log2;           // softmax scale * log2(e)

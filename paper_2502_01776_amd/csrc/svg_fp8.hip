@@ -196,7 +196,8 @@ struct Fp8Args {
   const uint8_t* labels;
   const int32_t* row_ptr[2];
   const int32_t* col_idx[2];
-  int N, nk, BH, nqt, total, reverse_q;
+  int N, nk, BH, nqt;
+  SparseOrder so;              // which workgroup takes which (head, query tile)
   float scale_log2;            // softmax scale * log2(e), before the quantisation scales
   int off, video_end, F, P, sink;
 };
@@ -204,13 +205,15 @@ struct Fp8Args {
 __global__ __launch_bounds__(256, 2) void attn_fp8_kernel(Fp8Args a) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kStageBytes];
 
-  // one contiguous chunk of (head, query tile) ids per XCD (see the bf16 kernel)
-  const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
-  const int lid = xcd * ((a.total + 7) >> 3) + loc;
-  if (lid >= a.total) return;
-  const int bh = lid / a.nqt;
-  int grp = lid - bh * a.nqt;
-  if (a.reverse_q) grp = a.nqt - 1 - grp;
+  // heavy query tiles first, then an eighth of each label's sequence of tiles (the same
+  // dispatch order as the bf16 kernel)
+  int bh = 0, grp = 0, pat = 0, cl = -1, head_cl0 = 0;
+  if (!sparse_slot(a.so, a.BH, a.labels, a.row_ptr[0], a.row_ptr[1], bh, grp, pat, cl, head_cl0)) return;
+  bh = __builtin_amdgcn_readfirstlane(bh);
+  grp = __builtin_amdgcn_readfirstlane(grp);
+  pat = __builtin_amdgcn_readfirstlane(pat);
+  cl = __builtin_amdgcn_readfirstlane(cl);
+  head_cl0 = __builtin_amdgcn_readfirstlane(head_cl0);
 
   const int tid = threadIdx.x;
   const int lane = tid & 63, wave = tid >> 6;
@@ -222,7 +225,6 @@ __global__ __launch_bounds__(256, 2) void attn_fp8_kernel(Fp8Args a) {
 
   // this lane's query: position qslot in the order the tile list refers to; for a temporal
   // head that is token off + f P + p with qslot = off + p F + f (q and o stay in token order)
-  const int pat = a.labels ? (a.labels[bh] != 0) : 0;
   const int qslot = grp * kBM + wave * 32 + r;
   const int qrow = min(qslot, a.N - 1);
   int io_row = qrow;
@@ -249,16 +251,10 @@ __global__ __launch_bounds__(256, 2) void attn_fp8_kernel(Fp8Args a) {
   const int lbeg = __builtin_amdgcn_readfirstlane(rp[grp]);
   const int lend = __builtin_amdgcn_readfirstlane(rp[grp + 1]);
   int lj = lbeg, lleft = lend - lbeg;
-  if (lleft > 1) {
+  if (lleft > 1 && cl >= 0) {
     const int first_video_tile = (a.off + kBN - 1) / kBN;
-    auto holds_text = [&](int gq) { return gq * kBM < a.off || (gq + 1) * kBM > a.video_end; };
     for (int cs = kCohort; cs >= 16; cs >>= 2) {
-      const int u0 = max(lid & ~(cs - 1), bh * a.nqt) - bh * a.nqt;
-      const int u1 = min(lid | (cs - 1), (bh + 1) * a.nqt - 1) - bh * a.nqt;
-      int top = a.reverse_q ? a.nqt - 1 - u0 : u1;
-      const int bottom = a.reverse_q ? a.nqt - 1 - u1 : u0;
-      while (top > bottom && holds_text(top)) --top;
-      if (holds_text(top)) break;
+      const int top = a.so.g_lo + min(cl | (cs - 1), head_cl0 + a.so.nl - 1) - head_cl0;
       int anchor = -1;
       for (int j = rp[top], e = min(rp[top + 1], rp[top] + 8); j < e; ++j)
         if (cols[j] >= first_video_tile) { anchor = cols[j]; break; }
@@ -502,11 +498,10 @@ int launch_fp8_attention(const Geo& g, const void* q8, const void* k8, const voi
   a.row_ptr[1] = row_ptr_t; a.col_idx[1] = col_idx_t;
   a.N = g.N; a.nk = g.nk; a.BH = g.B * g.H;
   a.nqt = g.nq;
-  a.total = a.BH * a.nqt;
-  a.reverse_q = (g.T > 0 && !g.text_first) ? 1 : 0;
+  a.so = sparse_order(a.BH, a.nqt, kBM, g.off, g.video_end, g.N);
   a.scale_log2 = g.scale * 1.4426950408889634f;
   a.off = g.off; a.video_end = g.video_end; a.F = g.F; a.P = g.P; a.sink = g.sink;
-  const unsigned grid = 8u * (unsigned)((a.total + 7) / 8);
+  const unsigned grid = sparse_grid(a.so, a.BH);
   (void)hipGetLastError();
   hipLaunchKernelGGL(attn_fp8_kernel, dim3(grid), dim3(256), 0, stream, a);
   return hip_status(hipGetLastError());
