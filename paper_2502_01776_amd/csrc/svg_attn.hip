@@ -284,42 +284,53 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     // as they run at the same pace they all want the same K/V tile at the same time.  The
     // order of the tiles does not change the result beyond fp32 summation order, and a
     // full list (every member starts at tile 0) is walked exactly like the dense kernel.
-    if (lleft > 1 && cl >= 0) {
-      const int first_video_tile = (a.off + BN - 1) / BN;      // tiles before it are text-prefix tiles
+    //   How many query tiles form a cohort follows from the geometry: the key window of the
+    // pattern, counted in list tiles, against the shift between neighbouring query tiles; the
+    // largest power of two (up to kCohort) for which the anchor still lies inside the window
+    // of every member.  Short windows (a few dozen tiles) get no common start at all: their
+    // workgroups live too briefly to spend memory round trips on finding one.
+    const int win_tiles = (int)min((pat ? (2LL * a.w_t + 1) * a.F : (2LL * a.w_s + 1) * a.P) * LT / BN, 1LL << 20);
+    int cs = kCohort;
+    while (cs > 1 && (cs - 1) * (BM * LT / BN) >= win_tiles) cs >>= 1;
+    if (lleft > 1 && cl >= 0 && cs >= 8) {
+      const int first_video_tile = (a.off + BN / LT - 1) / (BN / LT);      // tiles before it are text-prefix tiles
+      // cohort: the tiles of the same aligned block of cs in the label's sequence, as far as they
+      // belong to this head (none of them holds a text row; a tile that does starts at the
+      // beginning of its list, which is every key tile).  Member with the highest window: the
+      // last query tile of the cohort.
+      const int top = a.so.g_lo + min(cl | (cs - 1), head_cl0 + a.so.nl - 1) - head_cl0;
       // own first and last entry: a list is one run of consecutive tiles (the window) with the
       // text tiles in front of or behind it, so the place of a tile inside it can usually be
       // told from one of its ends without searching (every load saved here is a memory
-      // round trip in front of a workgroup whose whole list may be a few dozen tiles long)
+      // round trip in front of the first K/V tile)
       const int c_first = cols[lbeg], c_last = cols[lend - 1];
-      // cohort: the tiles of the same aligned block of cs in the label's sequence, as far as they
-      // belong to this head (none of them holds a text row; a tile that does starts at the
-      // beginning of its list, which is every key tile)
-      for (int cs = kCohort; cs >= 16; cs >>= 2) {
-        // member with the highest window: the last query tile of the cohort
-        const int top = a.so.g_lo + min(cl | (cs - 1), head_cl0 + a.so.nl - 1) - head_cl0;
-        // its first entry that is no text-prefix tile, among the first eight (loaded together)
-        const int tb = rp[top], te = rp[top + 1];
-        int cand[8];
+      // the top member's first entry that is no text-prefix tile, among the first eight (loaded together)
+      const int tb = rp[top], te = rp[top + 1];
+      int cand[8];
 #pragma unroll
-        for (int j = 0; j < 8; ++j) cand[j] = cols[min(tb + j, te - 1)];
-        int anchor = -1;
+      for (int j = 0; j < 8; ++j) cand[j] = cols[min(tb + j, te - 1)];
+      int anchor = -1;
 #pragma unroll
-        for (int j = 7; j >= 0; --j)
-          if (tb + j < te && cand[j] >= first_video_tile) anchor = cand[j];
-        if (anchor < 0) break;
+      for (int j = 7; j >= 0; --j)
+        if (tb + j < te && cand[j] >= first_video_tile) anchor = cand[j];
+      if (anchor >= c_first && anchor <= c_last) {
         // own entry == anchor: counted from the front, from the back, else by binary search
         const int from_front = anchor - c_first, from_back = (lleft - 1) - (c_last - anchor);
-        const bool front_ok = from_front >= 0 && from_front < lleft, back_ok = from_back >= 0 && from_back < lleft;
+        const bool front_ok = from_front < lleft, back_ok = from_back >= 0;
         const int at_front = cols[lbeg + (front_ok ? from_front : 0)];
         const int at_back = cols[lbeg + (back_ok ? from_back : 0)];
-        if (front_ok && at_front == anchor) { lj = lbeg + from_front; break; }
-        if (back_ok && at_back == anchor) { lj = lbeg + from_back; break; }
-        int lo = 0, hi = lleft;
-        while (lo < hi) {
-          const int mid = (lo + hi) >> 1;
-          if (cols[lbeg + mid] < anchor) lo = mid + 1; else hi = mid;
+        if (front_ok && at_front == anchor) {
+          lj = lbeg + from_front;
+        } else if (back_ok && at_back == anchor) {
+          lj = lbeg + from_back;
+        } else {
+          int lo = 0, hi = lleft;
+          while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (cols[lbeg + mid] < anchor) lo = mid + 1; else hi = mid;
+          }
+          if (lo < lleft && cols[lbeg + lo] == anchor) lj = lbeg + lo;
         }
-        if (lo < lleft && cols[lbeg + lo] == anchor) { lj = lbeg + lo; break; }
       }
       lj = __builtin_amdgcn_readfirstlane(lj);     // (uniform by construction: keeps the cursor scalar)
     }

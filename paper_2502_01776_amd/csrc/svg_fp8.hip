@@ -199,7 +199,7 @@ struct Fp8Args {
   int N, nk, BH, nqt;
   SparseOrder so;              // which workgroup takes which (head, query tile)
   float scale_log2;            // softmax scale * log2(e), before the quantisation scales
-  int off, video_end, F, P, sink;
+  int off, video_end, F, P, sink, w_s, w_t;
 };
 
 __global__ __launch_bounds__(256, 2) void attn_fp8_kernel(Fp8Args a) {
@@ -251,20 +251,30 @@ __global__ __launch_bounds__(256, 2) void attn_fp8_kernel(Fp8Args a) {
   const int lbeg = __builtin_amdgcn_readfirstlane(rp[grp]);
   const int lend = __builtin_amdgcn_readfirstlane(rp[grp + 1]);
   int lj = lbeg, lleft = lend - lbeg;
-  if (lleft > 1 && cl >= 0) {
+  // cohort size by geometry: the largest power of two for which the anchor lies inside every
+  // member's key window; short windows start at their own first tile
+  const int win_tiles = (int)min((pat ? (2LL * a.w_t + 1) * a.F : (2LL * a.w_s + 1) * a.P) / kBN, 1LL << 20);
+  int cs = kCohort;
+  while (cs > 1 && (cs - 1) * (kBM / kBN) >= win_tiles) cs >>= 1;
+  if (lleft > 1 && cl >= 0 && cs >= 8) {
     const int first_video_tile = (a.off + kBN - 1) / kBN;
-    for (int cs = kCohort; cs >= 16; cs >>= 2) {
-      const int top = a.so.g_lo + min(cl | (cs - 1), head_cl0 + a.so.nl - 1) - head_cl0;
-      int anchor = -1;
-      for (int j = rp[top], e = min(rp[top + 1], rp[top] + 8); j < e; ++j)
-        if (cols[j] >= first_video_tile) { anchor = cols[j]; break; }
-      if (anchor < 0) break;
+    const int top = a.so.g_lo + min(cl | (cs - 1), head_cl0 + a.so.nl - 1) - head_cl0;
+    const int c_first = cols[lbeg], c_last = cols[lend - 1];
+    int anchor = -1;
+    for (int j = rp[top], e = min(rp[top + 1], rp[top] + 8); j < e; ++j)
+      if (cols[j] >= first_video_tile) { anchor = cols[j]; break; }
+    if (anchor >= c_first && anchor <= c_last) {
       int lo = 0, hi = lleft;
-      while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (cols[lbeg + mid] < anchor) lo = mid + 1; else hi = mid;
+      const int from_front = anchor - c_first;
+      if (from_front < lleft && cols[lbeg + from_front] == anchor) {
+        lo = from_front;
+      } else {
+        while (lo < hi) {
+          const int mid = (lo + hi) >> 1;
+          if (cols[lbeg + mid] < anchor) lo = mid + 1; else hi = mid;
+        }
       }
-      if (lo < lleft && cols[lbeg + lo] == anchor) { lj = lbeg + lo; break; }
+      if (lo < lleft && cols[lbeg + lo] == anchor) lj = lbeg + lo;
     }
     lj = __builtin_amdgcn_readfirstlane(lj);
   }
@@ -501,6 +511,7 @@ int launch_fp8_attention(const Geo& g, const void* q8, const void* k8, const voi
   a.so = sparse_order(a.BH, a.nqt, kBM, g.off, g.video_end, g.N);
   a.scale_log2 = g.scale * 1.4426950408889634f;
   a.off = g.off; a.video_end = g.video_end; a.F = g.F; a.P = g.P; a.sink = g.sink;
+  a.w_s = g.w_s; a.w_t = g.w_t;
   const unsigned grid = sparse_grid(a.so, a.BH);
   (void)hipGetLastError();
   hipLaunchKernelGGL(attn_fp8_kernel, dim3(grid), dim3(256), 0, stream, a);
