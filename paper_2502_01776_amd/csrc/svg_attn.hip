@@ -66,20 +66,24 @@ constexpr int kCohort = 64;   // consecutive query tiles that share an XCD (and 
 constexpr int kPrefetch = 4;          // LDS operand reads kept in flight ahead of the products
 constexpr unsigned kRsrcFlags = 0x00020000u;   // raw buffer, 32-bit data format (gfx9 encoding)
 
+// Wavefronts per SIMD the register budget is set for.  Head dimension 128 fills 256 registers
+// (two wavefronts).  At head dimension 64 the accumulators are half as large and the dense and
+// sparse passes fit 168 registers: three workgroups per CU, whose wavefronts cover each other's
+// softmax phases (the longer phase at this head dimension) better than two workgroups with
+// twice the keys per barrier did (4-7 % less time).  The masked forms would spill there.
+constexpr int waves_per_simd(int D, int NW, int MODE) {
+  return NW != 4 ? 1 : (D == 64 && (MODE == kDense || MODE == kSparse)) ? 3 : 2;
+}
+
 template <int D, int NW, int BN, int MODE>
-__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs a) {
+__global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_kernel(AttnArgs a) {
   constexpr int BM = 32 * NW;            // query rows per workgroup = rows of a query tile
   constexpr int THREADS = 64 * NW;
   constexpr int CPR = D / 8;             // 16-byte pieces per row
   constexpr int KB = BN / 32;            // 32-key blocks per tile
-  // Tile lists always refer to 64-key tiles.  A kernel whose key tile is 128 keys wide
-  // (head dimension 64: twice the products per barrier) walks the list in pairs: an entry
-  // of the cursor is (128-key tile index) * 4 + (which 64-key halves of it are kept).
-  constexpr int LT = BN == 128 ? 2 : 1;
   // kSparseExact is kSparse with the head's element mask applied inside every visited tile
   constexpr bool SPARSE = MODE == kSparse || MODE == kSparseExact;
   constexpr bool MASKABLE = MODE == kProfile || MODE == kSparseExact;
-  static_assert(LT == 1 || !MASKABLE, "the masked forms use list-sized key tiles");
   constexpr int DS = D / 16;             // k-steps of the first product
   constexpr int DB = D / 32;             // 32-row blocks of O^T
   constexpr int K_PIECES = BN * CPR;
@@ -289,11 +293,11 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     // largest power of two (up to kCohort) for which the anchor still lies inside the window
     // of every member.  Short windows (a few dozen tiles) get no common start at all: their
     // workgroups live too briefly to spend memory round trips on finding one.
-    const int win_tiles = (int)min((pat ? (2LL * a.w_t + 1) * a.F : (2LL * a.w_s + 1) * a.P) * LT / BN, 1LL << 20);
+    const int win_tiles = (int)min((pat ? (2LL * a.w_t + 1) * a.F : (2LL * a.w_s + 1) * a.P) / BN, 1LL << 20);
     int cs = kCohort;
-    while (cs > 1 && (cs - 1) * (BM * LT / BN) >= win_tiles) cs >>= 1;
+    while (cs > 1 && (cs - 1) * (BM / BN) >= win_tiles) cs >>= 1;
     if (lleft > 1 && cl >= 0 && cs >= 8) {
-      const int first_video_tile = (a.off + BN / LT - 1) / (BN / LT);      // tiles before it are text-prefix tiles
+      const int first_video_tile = (a.off + BN - 1) / BN;      // tiles before it are text-prefix tiles
       // cohort: the tiles of the same aligned block of cs in the label's sequence, as far as they
       // belong to this head (none of them holds a text row; a tile that does starts at the
       // beginning of its list, which is every key tile).  Member with the highest window: the
@@ -335,7 +339,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
       lj = __builtin_amdgcn_readfirstlane(lj);     // (uniform by construction: keeps the cursor scalar)
     }
   } else if (MODE == kDense) {
-    lend = (a.nk + LT - 1) / LT;
+    lend = a.nk;
   }
   const int c_lo = MODE == kProfile ? wg_range[0] : 0, c_hi = MODE == kProfile ? wg_range[1] : -1;
   int pseg = 0, pj = 0, pjb = -1;
@@ -382,38 +386,22 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
   // for the value on the spot, which would also wait for every staging load in flight).
   int lane_zero = 0;
   asm volatile("" : "+v"(lane_zero));
-  int pend0 = kNoTile, pend1 = kNoTile;
+  int pend0 = kNoTile;
   auto fetch_begin = [&]() {
-    if (SPARSE) {
-      pend0 = lleft > 0 ? cols[lj + lane_zero] : kNoTile;
-      if (LT == 2) {      // the entry after it: may be the upper half of the same 128-key tile
-        const int lj1 = lj + 1 == lend ? lbeg : lj + 1;
-        pend1 = lleft > 1 ? cols[lj1 + lane_zero] : kNoTile;
-      }
-    }
+    if (SPARSE) pend0 = lleft > 0 ? cols[lj + lane_zero] : kNoTile;
   };
   auto fetch_end = [&]() -> int {
     if (SPARSE) {
       if (lleft <= 0) return kNoTile;
       const int c = __builtin_amdgcn_readfirstlane(pend0);
-      int taken = 1, entry = c;
-      if (LT == 2) {
-        int halves = 1 << (c & 1);
-        if ((c & 1) == 0 && lleft > 1 && __builtin_amdgcn_readfirstlane(pend1) == c + 1) {
-          halves = 3;       // its upper half follows: one full tile
-          taken = 2;
-        }
-        entry = (c >> 1) * 4 + halves;
-      }
-      lleft -= taken;
-      lj += taken;
-      if (lj >= lend) lj -= lend - lbeg;
-      return entry;
+      --lleft;
+      if (++lj >= lend) lj = lbeg;
+      return c;
     }
     if (MODE == kDense) {
       const int j = lj++;
       if (j >= lend) return kNoTile;
-      return LT == 1 ? j : j * 4 + 3;
+      return j;
     }
     while (pj > pjb) {       // profile: move to the next interval that still has tiles
       int k0, k1;
@@ -454,7 +442,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
 
   auto load_tile = [&](int col_any) {
     // the tile index is the same in every lane; saying so keeps the descriptors scalar
-    const int key0 = __builtin_amdgcn_readfirstlane(LT == 1 ? col_any : col_any >> 2) * BN;
+    const int key0 = __builtin_amdgcn_readfirstlane(col_any) * BN;
     const unsigned bytes_left = (unsigned)(a.N - key0) * (D * 2);
     const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<__bf16*>(kh + (size_t)key0 * D), 0, bytes_left, kRsrcFlags);
@@ -633,8 +621,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
     col2 = col3;
     fetch_begin();
     if (next_col != kNoTile) load_tile(next_col);
-    const int tile = LT == 1 ? col : col >> 2;          // key tile of this iteration, BN keys wide
-    const int halves = LT == 1 ? 3 : (col & 3);
+    const int tile = col;          // key tile of this iteration
 
     // profile: does this wavefront need the tile at all, and does it need per-element masks?
     bool skip = false, need_masks = MASKABLE && masked;
@@ -709,7 +696,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
               }
             }
         }
-      } else if (ragged && (LT == 1 ? col == a.nk - 1 : (tile + 1) * BN > a.N)) {
+      } else if (ragged && col == a.nk - 1) {
         int lim = a.N - tile * BN - 4 * g;     // keys with 32 kb + 8 i + jj >= lim are out of range
         // opaque to the optimiser: keeps this rarely taken masking code inside the
         // branch instead of being speculated into every tile
@@ -722,17 +709,6 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void attn_kernel(AttnArgs
             for (int jj = 0; jj < 4; ++jj)
               if (kb * 32 + 8 * i + jj >= lim) sacc[kb][4 * i + jj] = -INFINITY;
       }
-      if (LT == 2 && halves != 3) {
-        // only one 64-key half of this tile is on the list: the other takes no part
-        int hv = halves;
-        asm volatile("" : "+v"(hv));      // (keeps the selects below inside this branch)
-#pragma unroll
-        for (int kb = 0; kb < KB; ++kb)
-#pragma unroll
-          for (int e = 0; e < 16; ++e)
-            if (((hv >> (kb >> 1)) & 1) == 0) sacc[kb][e] = -INFINITY;
-      }
-
       // ---- online softmax: one query per lane.
       // Fast path: exponentials are taken against the current reference m_run without
       // looking at the tile's maximum.  That is the same softmax as long as nothing
@@ -999,11 +975,8 @@ int launch_one(AttnArgs a, int rows_total, hipStream_t stream) {
 template <int MODE>
 int dispatch(const Geo& g, const AttnArgs& a, int rows_total, hipStream_t stream) {
   if (g.bm == 128) {
-    if (g.D == 128) return launch_one<128, 4, 64, MODE>(a, rows_total, stream);
-    // head dimension 64: half the products per key, so the dense and sparse passes take
-    // 128 keys per barrier (the tile list still counts 64-key tiles)
-    if constexpr (MODE == kProfile || MODE == kSparseExact) return launch_one<64, 4, 64, MODE>(a, rows_total, stream);
-    else return launch_one<64, 4, 128, MODE>(a, rows_total, stream);
+    return g.D == 128 ? launch_one<128, 4, 64, MODE>(a, rows_total, stream)
+                      : launch_one<64, 4, 64, MODE>(a, rows_total, stream);
   }
   return g.D == 128 ? launch_one<128, 1, 32, MODE>(a, rows_total, stream)
                     : launch_one<64, 1, 32, MODE>(a, rows_total, stream);
