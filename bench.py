@@ -47,6 +47,9 @@ def parse():
     ap.add_argument("--without-layout-transform", action="store_true",
                     help="also time the comparison arm of Sec. 5.5: temporal heads left in frame-major order "
                          "with the frame-major temporal tile list (no layout kernels)")
+    ap.add_argument("--kv-in-kernel", action="store_true",
+                    help="no layout pass at all: k and v stay in token order and the sparse kernel gathers the "
+                         "rows of a temporal head's key tiles itself (SVG_ATTN_KV_TOKEN_ORDER)")
     ap.add_argument("--four-layout-passes", action="store_true",
                     help="time the pipeline with q, k, v and o all going through the layout kernels, instead of "
                          "the default where the attention kernel gathers q rows and scatters o rows itself")
@@ -258,7 +261,11 @@ def main():
 
     folded = not args.four_layout_passes
 
+    in_kernel = args.kv_in_kernel and folded
+
     def stage_layout_fwd():
+        if in_kernel:
+            return
         if folded:
             S.svg_layout_kv_temporal(sh, k, v, kp, vp, labels)
         else:
@@ -267,7 +274,11 @@ def main():
             S.svg_layout_fwd(sh, v, vp, labels)
 
     def stage_sparse():
-        if folded:
+        if in_kernel:
+            S.svg_sparse_attn_fwd_ex(sh, q, k, v, o, labels, *lists,
+                                     flags=S.SVG_ATTN_QO_TOKEN_ORDER | S.SVG_ATTN_KV_TOKEN_ORDER,
+                                     workspace=ws, workspace_bytes=ws_bytes)
+        elif folded:
             S.svg_sparse_attn_fwd_kv2(sh, q, k, v, kp, vp, o, labels, *lists)
         else:
             S.svg_sparse_attn_fwd(sh, qp, kp, vp, op, labels, *lists)
@@ -382,7 +393,8 @@ def main():
         "speedup_vs_dense": None if dense_ms is None else dense_ms / wall_ms,
         "layout_passes": "k and v of temporal heads in one launch (q and o inside the attention kernel, spatial heads "
                          "read in place)" if folded else "q k v o, all heads",
-        "layout_gbs": {"fwd": (2 if folded else 3) * layout_bytes / (breakdown["layout_fwd"] * 1e-3) / 1e9,
+        "layout_gbs": {"fwd": None if in_kernel else
+                       (2 if folded else 3) * layout_bytes / (breakdown["layout_fwd"] * 1e-3) / 1e9,
                        "counts": "rows of temporal heads only, read + write",
                        "inv_o": None if folded else layout_bytes / (breakdown["layout_inv"] * 1e-3) / 1e9},
         # the three masked passes of Alg. 1 counted in full (3 x 4 t N D per head), although the
@@ -543,6 +555,30 @@ def main():
                           "workspace_mb": nb / 1e6})
             del wsp
         out["profile_ratio_sweep"] = sweep
+    if folded and not in_kernel and cfg["block_m"] == 128:
+        # the same layer with no layout pass and no second copy of k, v: the sparse kernel gathers the
+        # rows of a temporal head's key tiles itself (same labels, bit-identical output)
+        o_g = torch.empty_like(o)
+        both = S.SVG_ATTN_QO_TOKEN_ORDER | S.SVG_ATTN_KV_TOKEN_ORDER
+        for _ in range(2):
+            S.svg_sparse_attn_fwd_ex(sh, q, k, v, o_g, labels, *lists, flags=both, workspace=ws, workspace_bytes=ws_bytes)
+        torch.cuda.synchronize()
+        times = []
+        for _ in range(args.steps):
+            e0, e1 = ev(), ev()
+            e0.record()
+            S.svg_sparse_attn_fwd_ex(sh, q, k, v, o_g, labels, *lists, flags=both, workspace=ws, workspace_bytes=ws_bytes)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+        ms_g = float(np.median(times))
+        out["kv_gathered_in_kernel"] = {
+            "sparse_attn_ms": ms_g, "ms_per_layer": breakdown["profile"] + ms_g,
+            "against_layout_pass_plus_kernel_ms": breakdown["layout_fwd"] + breakdown["sparse_attn"],
+            "output_equal_bit_for_bit": bool(torch.equal(o_g.view(torch.int16), o.view(torch.int16))),
+            "extra_device_memory_bytes": 8 * nk * cfg["block_n"],
+            "extra_device_memory_bytes_with_layout_pass": 2 * q.numel() * 2}
+        del o_g
     if args.without_layout_transform:
         # same labels, same kernel, unpermuted q, k, v: the temporal slot gets the list of the
         # temporal mask in frame-major order

@@ -193,9 +193,19 @@ int svg_sparse_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, 
  * inside every visited tile, so that the result is attention under the exact mask
  * instead of its block cover.  The tile list still decides which tiles are visited (with
  * the lists of svg_tile_list_build no kept element is lost); temporal heads are expected in
- * P-outer order as usual.  Unknown flag bits: SVG_ERR_INVALID_ARG.
+ * P-outer order as usual.
+ * SVG_ATTN_KV_TOKEN_ORDER folds the remaining two layout passes into the kernel as well
+ * (Sec. 4.3): k and v of EVERY head stay in the original token order, and a temporal head's
+ * key tile is gathered row by row (a row is 2*D contiguous bytes) from where the
+ * transformation of Sec. 4.2 would have taken it.  Together with SVG_ATTN_QO_TOKEN_ORDER no
+ * layout pass and no second copy of any tensor is left; results are bit-identical to the
+ * passes it replaces.  It needs workspace_bytes >= 8 * nk * block_n (nk from svg_tile_counts;
+ * svg_workspace_bytes covers it) for the table of source rows, which the call itself fills
+ * (SVG_ERR_WORKSPACE if NULL or too small, SVG_ERR_ALIAS if it overlaps a tensor), and
+ * block_m = 128; combined with SVG_ATTN_ELEMENT_MASK or block_m = 32: SVG_ERR_UNSUPPORTED.
+ * Unknown flag bits: SVG_ERR_INVALID_ARG.
  */
-enum { SVG_ATTN_QO_TOKEN_ORDER = 1, SVG_ATTN_ELEMENT_MASK = 2 };
+enum { SVG_ATTN_QO_TOKEN_ORDER = 1, SVG_ATTN_ELEMENT_MASK = 2, SVG_ATTN_KV_TOKEN_ORDER = 4 };
 int svg_sparse_attn_fwd_ex(const svg_shape_t* shape, const void* q, const void* k, const void* v,
                            void* o, const uint8_t* labels, const int32_t* row_ptr_s,
                            const int32_t* col_idx_s, const int32_t* row_ptr_t,

@@ -24,6 +24,7 @@ SVG_ROPE_INTERLEAVED, SVG_ROPE_HALF = 0, 1
 SVG_FP8_Q, SVG_FP8_K, SVG_FP8_VT, SVG_FP8_SCALES = 0, 1, 2, 3   # svg_fp8_buffer_bytes
 SVG_ATTN_QO_TOKEN_ORDER = 1          # svg_sparse_attn_fwd_ex: q read and o written in token order
 SVG_ATTN_ELEMENT_MASK = 2            # svg_sparse_attn_fwd_ex: the pattern's element mask inside every visited tile
+SVG_ATTN_KV_TOKEN_ORDER = 4          # svg_sparse_attn_fwd_ex: k, v of temporal heads stay in token order (gathered in the kernel)
 SVG_OK = 0
 
 EXPORTS = ("svg_strerror", "svg_version", "svg_last_hip_error", "svg_workspace_bytes", "svg_tile_counts",

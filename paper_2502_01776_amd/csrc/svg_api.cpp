@@ -63,9 +63,8 @@ int svg_sparse_attn_fwd_ex(const svg_shape_t* shape, const void* q, const void* 
                            const int32_t* col_idx_s, const int32_t* row_ptr_t,
                            const int32_t* col_idx_t, uint32_t flags, void* workspace,
                            size_t workspace_bytes, void* stream) {
-  (void)workspace;
-  (void)workspace_bytes;
-  if (flags & ~(uint32_t)(SVG_ATTN_QO_TOKEN_ORDER | SVG_ATTN_ELEMENT_MASK)) return SVG_ERR_INVALID_ARG;
+  if (flags & ~(uint32_t)(SVG_ATTN_QO_TOKEN_ORDER | SVG_ATTN_ELEMENT_MASK | SVG_ATTN_KV_TOKEN_ORDER))
+    return SVG_ERR_INVALID_ARG;
   Geo g;
   int rc = svg::make_geo(shape, &g);
   if (rc != SVG_OK) return rc;
@@ -75,9 +74,18 @@ int svg_sparse_attn_fwd_ex(const svg_shape_t* shape, const void* q, const void* 
   if (labels && (!row_ptr_t || !col_idx_t)) return SVG_ERR_INVALID_ARG;
   const size_t bytes = tensor_bytes(g);
   if (overlap(o, q, bytes) || overlap(o, k, bytes) || overlap(o, v, bytes)) return SVG_ERR_ALIAS;
+  int32_t* row_table = nullptr;
+  if (flags & SVG_ATTN_KV_TOKEN_ORDER) {
+    if ((flags & SVG_ATTN_ELEMENT_MASK) || g.bm != 128) return SVG_ERR_UNSUPPORTED;
+    if (!workspace || svg::misaligned16(workspace) || workspace_bytes < svg::row_table_bytes(g)) return SVG_ERR_WORKSPACE;
+    if (overlap(workspace, svg::row_table_bytes(g), o, bytes) || overlap(workspace, svg::row_table_bytes(g), q, bytes) ||
+        overlap(workspace, svg::row_table_bytes(g), k, bytes) || overlap(workspace, svg::row_table_bytes(g), v, bytes))
+      return SVG_ERR_ALIAS;
+    row_table = static_cast<int32_t*>(workspace);
+  }
   return svg::launch_attention(g, q, k, v, nullptr, nullptr, o, labels, row_ptr_s, col_idx_s, row_ptr_t, col_idx_t,
                                true, (flags & SVG_ATTN_QO_TOKEN_ORDER) != 0,
-                               (flags & SVG_ATTN_ELEMENT_MASK) != 0, static_cast<hipStream_t>(stream));
+                               (flags & SVG_ATTN_ELEMENT_MASK) != 0, row_table, static_cast<hipStream_t>(stream));
 }
 
 int svg_layout_kv_temporal(const svg_shape_t* shape, const void* k, const void* v, void* k_t, void* v_t,
@@ -112,7 +120,7 @@ int svg_sparse_attn_fwd_kv2(const svg_shape_t* shape, const void* q, const void*
       overlap(o, v_t, bytes))
     return SVG_ERR_ALIAS;
   return svg::launch_attention(g, q, k, v, k_t, v_t, o, labels, row_ptr_s, col_idx_s, row_ptr_t, col_idx_t, true,
-                               true, (flags & SVG_ATTN_ELEMENT_MASK) != 0, static_cast<hipStream_t>(stream));
+                               true, (flags & SVG_ATTN_ELEMENT_MASK) != 0, nullptr, static_cast<hipStream_t>(stream));
 }
 
 int svg_sparse_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, const void* v,
@@ -136,7 +144,7 @@ int svg_dense_attn_fwd(const svg_shape_t* shape, const void* q, const void* k, c
   const size_t bytes = tensor_bytes(g);
   if (overlap(o, q, bytes) || overlap(o, k, bytes) || overlap(o, v, bytes)) return SVG_ERR_ALIAS;
   return svg::launch_attention(g, q, k, v, nullptr, nullptr, o, nullptr, nullptr, nullptr, nullptr, nullptr, false,
-                               false, false, static_cast<hipStream_t>(stream));
+                               false, false, nullptr, static_cast<hipStream_t>(stream));
 }
 
 int svg_qk_norm_rope(const svg_shape_t* shape, const void* x, void* y, int norm, const float* weight,

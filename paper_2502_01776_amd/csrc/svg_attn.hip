@@ -72,7 +72,7 @@ constexpr unsigned kRsrcFlags = 0x00020000u;   // raw buffer, 32-bit data format
 // softmax phases (the longer phase at this head dimension) better than two workgroups with
 // twice the keys per barrier did (4-7 % less time).  The masked forms would spill there.
 constexpr int waves_per_simd(int D, int NW, int MODE) {
-  return NW != 4 ? 1 : (D == 64 && (MODE == kDense || MODE == kSparse)) ? 3 : 2;
+  return NW != 4 ? 1 : (D == 64 && (MODE == kDense || MODE == kSparse || MODE == kSparseGather)) ? 3 : 2;
 }
 
 template <int D, int NW, int BN, int MODE>
@@ -82,7 +82,11 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
   constexpr int CPR = D / 8;             // 16-byte pieces per row
   constexpr int KB = BN / 32;            // 32-key blocks per tile
   // kSparseExact is kSparse with the head's element mask applied inside every visited tile
-  constexpr bool SPARSE = MODE == kSparse || MODE == kSparseExact;
+  // kSparseGather is kSparse with k and v of the temporal heads left in token order: the rows of
+  // a key tile are fetched from where the layout transformation would have taken them
+  constexpr bool SPARSE = MODE == kSparse || MODE == kSparseExact || MODE == kSparseGather;
+  constexpr bool GATHER = MODE == kSparseGather;
+  static_assert(!GATHER || NW == 4, "the gathering form exists for 128-row query tiles");
   constexpr bool MASKABLE = MODE == kProfile || MODE == kSparseExact;
   constexpr int DS = D / 16;             // k-steps of the first product
   constexpr int DB = D / 32;             // 32-row blocks of O^T
@@ -440,7 +444,44 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
   const int k_stage_off = SPLIT ? ((tid / CPR) * D + (tid % CPR) * 8) * 2 : 0;
   const int v_stage_off = SPLIT ? (v_key((tid >> 1) / CPR, 4 * (tid & 1)) * D + ((tid >> 1) % CPR) * 8) * 2 : 0;
 
+  // Gathering form: every K/V row is fetched through a table of source rows.  For a temporal
+  // head row v of the P-outer order is token row_table[entries + v] (Sec. 4.2; text rows map to
+  // themselves); a spatial head uses the identity half row_table[v], so that both kinds run the
+  // same instructions.  Rows beyond N map to a row outside the tensor, which the bounds-checked
+  // loads return as zero.  The entries of a tile are loaded one tile ahead of its K/V rows; a
+  // row is 2 D contiguous bytes, so the loads stay whole cache lines.
+  const int tab_base = GATHER && pat != 0 ? a.nk * BN * 4 : 0;
+  int tabk[GATHER ? K_PER_THREAD : 1];
+  i32x4 tabv = {0, 0, 0, 0};
+  auto load_table = [&](int col_any) {
+    const int key0 = __builtin_amdgcn_readfirstlane(col_any) * BN;
+    const __amdgpu_buffer_rsrc_t rt = __builtin_amdgcn_make_buffer_rsrc(
+        const_cast<int32_t*>(a.row_table), 0, 2u * (unsigned)a.nk * BN * 4u, kRsrcFlags);
+#pragma unroll
+    for (int i = 0; i < K_PER_THREAD; ++i)
+      tabk[i] = __builtin_amdgcn_raw_buffer_load_b32(rt, (tid / CPR + i * (THREADS / CPR)) * 4, tab_base + key0 * 4, 0);
+    if (v_role) {
+      const u32x4 tv = __builtin_amdgcn_raw_buffer_load_b128(rt, v_key((tid >> 1) / CPR, 4 * (tid & 1)) * 4, tab_base + key0 * 4, 0);
+      tabv = i32x4{(int)tv[0], (int)tv[1], (int)tv[2], (int)tv[3]};
+    }
+  };
+
   auto load_tile = [&](int col_any) {
+    if constexpr (GATHER) {
+      const unsigned head_bytes = (unsigned)a.N * (D * 2);
+      const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(kh), 0, head_bytes, kRsrcFlags);
+      const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(vh), 0, head_bytes, kRsrcFlags);
+      const int piece_k = (tid % CPR) * 16, piece_v = ((tid >> 1) % CPR) * 16;
+#pragma unroll
+      for (int i = 0; i < K_PER_THREAD; ++i)
+        kst[i] = __builtin_amdgcn_raw_buffer_load_b128(rk, tabk[i] * (D * 2) + piece_k, 0, 0);
+      if (v_role) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+          vst[0][e] = __builtin_amdgcn_raw_buffer_load_b128(rv, tabv[e] * (D * 2) + piece_v, 0, 0);
+      }
+      return;
+    }
     // the tile index is the same in every lane; saying so keeps the descriptors scalar
     const int key0 = __builtin_amdgcn_readfirstlane(col_any) * BN;
     const unsigned bytes_left = (unsigned)(a.N - key0) * (D * 2);
@@ -592,9 +633,11 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
   // tile's barrier and the next tile's global loads
   int col = next_tile(), col1 = next_tile(), col2 = next_tile(), col3 = next_tile();
   if (col != kNoTile) {
+    if (GATHER) load_table(col);
     load_tile(col);
     store_tile(0, col);
   }
+  if (GATHER && col1 != kNoTile) load_table(col1);
   __syncthreads();
 
   // Touch Q here so that its loads are known to have completed before the loop.  Without
@@ -621,6 +664,7 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
     col2 = col3;
     fetch_begin();
     if (next_col != kNoTile) load_tile(next_col);
+    if (GATHER && col1 != kNoTile) load_table(col1);      // entries of the tile after it
     const int tile = col;          // key tile of this iteration
 
     // profile: does this wavefront need the tile at all, and does it need per-element masks?
@@ -964,7 +1008,7 @@ int launch_one(AttnArgs a, int rows_total, hipStream_t stream) {
   a.nqt = (rows_total + BM - 1) / BM;
   a.total = a.BH * a.nqt;
   const unsigned per_xcd = (unsigned)((a.total + 8 * kCohort - 1) / (8 * kCohort)) * kCohort;   // dense
-  if (MODE == kSparse || MODE == kSparseExact) a.so = sparse_order(a.BH, a.nqt, BM, a.off, a.video_end, a.N);
+  if (MODE == kSparse || MODE == kSparseExact || MODE == kSparseGather) a.so = sparse_order(a.BH, a.nqt, BM, a.off, a.video_end, a.N);
   const unsigned grid = MODE == kProfile ? (unsigned)(8 * (a.nsplit + 2) * ((a.total + 7) / 8))
                         : MODE == kDense ? 8u * per_xcd : sparse_grid(a.so, a.BH);
   (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
@@ -978,8 +1022,23 @@ int dispatch(const Geo& g, const AttnArgs& a, int rows_total, hipStream_t stream
     return g.D == 128 ? launch_one<128, 4, 64, MODE>(a, rows_total, stream)
                       : launch_one<64, 4, 64, MODE>(a, rows_total, stream);
   }
-  return g.D == 128 ? launch_one<128, 1, 32, MODE>(a, rows_total, stream)
-                    : launch_one<64, 1, 32, MODE>(a, rows_total, stream);
+  if constexpr (MODE == kSparseGather) return SVG_ERR_UNSUPPORTED;
+  else return g.D == 128 ? launch_one<128, 1, 32, MODE>(a, rows_total, stream)
+                         : launch_one<64, 1, 32, MODE>(a, rows_total, stream);
+}
+
+// Source rows for the gathering form: table[v] = v (spatial heads), table[entries + v] = token
+// row of row v of the P-outer order (text rows: themselves); padding: a row outside the tensor.
+__global__ void row_table_kernel(int32_t* table, int entries, int N, int off, int video_end, int F, int P, int sink) {
+  const int v = blockIdx.x * blockDim.x + threadIdx.x;
+  if (v >= entries) return;
+  int same = 0x00ffffff, moved = 0x00ffffff;
+  if (v < N) {
+    same = v;
+    moved = v >= off && v < video_end ? off + (int)transformed_to_token((unsigned)(v - off), (unsigned)F, (unsigned)P, sink) : v;
+  }
+  table[v] = same;
+  table[entries + v] = moved;
 }
 
 AttnArgs base_args(const Geo& g, const void* q, const void* k, const void* v, void* o) {
@@ -1000,7 +1059,7 @@ AttnArgs base_args(const Geo& g, const void* q, const void* k, const void* v, vo
 int launch_attention(const Geo& g, const void* q, const void* k, const void* v, const void* k_t, const void* v_t,
                      void* o, const uint8_t* labels, const int32_t* row_ptr_s, const int32_t* col_idx_s,
                      const int32_t* row_ptr_t, const int32_t* col_idx_t, bool sparse,
-                     bool qo_token_order, bool element_mask, hipStream_t stream) {
+                     bool qo_token_order, bool element_mask, int32_t* row_table, hipStream_t stream) {
   AttnArgs a = base_args(g, q, k, v, o);
   a.k_t = static_cast<const __bf16*>(k_t);
   a.v_t = static_cast<const __bf16*>(v_t);
@@ -1008,6 +1067,18 @@ int launch_attention(const Geo& g, const void* q, const void* k, const void* v, 
   a.qo_token_order = sparse && qo_token_order ? 1 : 0;
   a.row_ptr[0] = row_ptr_s; a.col_idx[0] = col_idx_s;
   a.row_ptr[1] = row_ptr_t; a.col_idx[1] = col_idx_t;
+  if (sparse && row_table) {
+    // k and v in token order: build the row table, then the gathering form
+    if (element_mask || g.bm != 128) return SVG_ERR_UNSUPPORTED;
+    const int entries = g.nk * g.bn;
+    (void)hipGetLastError();
+    hipLaunchKernelGGL(row_table_kernel, dim3((entries + 255) / 256), dim3(256), 0, stream, row_table, entries, g.N,
+                       g.off, g.video_end, g.F, g.P, g.sink);
+    const int rc = hip_status(hipGetLastError());
+    if (rc != SVG_OK) return rc;
+    a.row_table = row_table;
+    return dispatch<kSparseGather>(g, a, g.N, stream);
+  }
   if (sparse && element_mask) return dispatch<kSparseExact>(g, a, g.N, stream);
   return sparse ? dispatch<kSparse>(g, a, g.N, stream) : dispatch<kDense>(g, a, g.N, stream);
 }

@@ -15,7 +15,7 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 
-enum Mode { kDense = 0, kSparse = 1, kProfile = 2, kSparseExact = 3 };
+enum Mode { kDense = 0, kSparse = 1, kProfile = 2, kSparseExact = 3, kSparseGather = 4 };
 
 constexpr int kCodeDrop = 0x7fffffff;   // key beyond N: never kept
 constexpr int kCodeKeep = 0x7ffffffe;   // text key / sink key: kept by every query
@@ -133,6 +133,7 @@ struct AttnArgs {
   const __bf16* v_t;
   void* o;                    // bf16 [B,H,N,D] (dense, sparse) or fp32 [3][BH][t][D] (profile)
   const uint8_t* labels;      // sparse: per-head pattern, may be null
+  const int32_t* row_table;   // gathering sparse form: token row of every P-outer row, nk * BN entries
   const int32_t* row_ptr[2];
   const int32_t* col_idx[2];
   const int32_t* rows;        // profile: sampled rows

@@ -67,7 +67,8 @@ const char* svg_last_hip_error(void) { return hipGetErrorString(svg::g_last_hip_
 size_t svg_workspace_bytes(const svg_shape_t* shape, int32_t t) {
   Geo g;
   if (svg::make_geo(shape, &g) != SVG_OK || t <= 0) return 0;
-  return svg::profile_workspace_bytes(g, t);
+  const size_t a = svg::profile_workspace_bytes(g, t), b = svg::row_table_bytes(g);
+  return a > b ? a : b;
 }
 
 int svg_tile_counts(const svg_shape_t* shape, int32_t* nq, int32_t* nk) {

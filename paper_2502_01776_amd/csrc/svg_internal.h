@@ -96,7 +96,10 @@ int launch_layout(const Geo& g, const void* in, void* out, const void* in2, void
 int launch_attention(const Geo& g, const void* q, const void* k, const void* v, const void* k_t, const void* v_t,
                      void* o, const uint8_t* labels, const int32_t* row_ptr_s, const int32_t* col_idx_s,
                      const int32_t* row_ptr_t, const int32_t* col_idx_t, bool sparse,
-                     bool qo_token_order, bool element_mask, hipStream_t stream);
+                     bool qo_token_order, bool element_mask, int32_t* row_table, hipStream_t stream);
+
+// Bytes of workspace the sparse pass needs when k and v stay in token order (the row table).
+inline size_t row_table_bytes(const Geo& g) { return 2 * (size_t)g.nk * g.bn * sizeof(int32_t); }
 int launch_profile(const Geo& g, const void* q, const void* k, const void* v, const int32_t* rows,
                    int t, uint8_t* labels, float* mse, float* workspace, hipStream_t stream);
 

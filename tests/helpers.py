@@ -79,6 +79,22 @@ def gpu_layer_kv2(shape, q, k, v, labels, lists=None, flags=0, fill=None):
     return o, kt, vt
 
 
+def gpu_layer_in_place(shape, q, k, v, labels, lists=None, canary=64):
+    """The sparse pass with no layout pass at all: q, k, v, o of every head in token order, the rows of
+    a temporal head's tiles gathered by the kernel.  The workspace (the row table) is given at its
+    exact size with guard bytes behind it.  Returns (o, guard bytes intact)."""
+    lists = lists or device_tile_lists(shape)
+    nq, nk = S.svg_tile_counts(shape)
+    need = 8 * nk * shape.block_n
+    ws = torch.full((need + canary,), 0x5A, dtype=torch.uint8, device="cuda")
+    o = torch.empty_like(q)
+    S.svg_sparse_attn_fwd_ex(shape, q, k, v, o, labels, *lists,
+                             flags=S.SVG_ATTN_QO_TOKEN_ORDER | S.SVG_ATTN_KV_TOKEN_ORDER,
+                             workspace=ws, workspace_bytes=need)
+    torch.cuda.synchronize()
+    return o, bool((ws[need:] == 0x5A).all())
+
+
 def assert_attn_close(got: torch.Tensor, ref: np.ndarray, what=""):
     g = f64(got)
     assert np.isfinite(g).all(), f"{what}: non-finite output"

@@ -212,6 +212,15 @@ def test_pointer_checks_without_gpu():
     assert kv2(q_, k_, v_, kt_, vt_, o_, a, a, a, a, a, 1, None) == -1             # token order is implied, not a flag
     assert kv2(q_, k_, v_, kt_, vt_, kt_ + 32, a, a, a, a, a, 0, None) == -4
     assert kv2(q_, k_, v_, kt_, vt_, q_, a, a, a, a, a, 2, None) == -4
+    # k and v left in token order (rows gathered by the kernel): needs the row table's workspace
+    ex = lambda *args: lib.svg_sparse_attn_fwd_ex(C.byref(sh), *args)
+    need = 8 * sh.block_n * (-(-(sh.F * sh.P + sh.T) // sh.block_n))
+    ws_ = far[6]
+    assert ex(q_, k_, v_, o_, a, a, a, a, a, 5, None, 0, None) == -3
+    assert ex(q_, k_, v_, o_, a, a, a, a, a, 5, ws_, need - 1, None) == -3
+    assert ex(q_, k_, v_, o_, a, a, a, a, a, 5, o_ + 64, need, None) == -4          # table inside o
+    assert ex(q_, k_, v_, o_, a, a, a, a, a, 7, ws_, need, None) == -2              # no exact-mask form of it
+    assert ex(q_, k_, v_, o_, a, a, a, a, a, 8, ws_, need, None) == -1              # unknown flag
     lkv = lambda *args: lib.svg_layout_kv_temporal(C.byref(sh), *args)
     assert lkv(k_, v_, kt_, None, a, None) == -1
     assert lkv(k_, v_, kt_, vt_, None, None) == -1

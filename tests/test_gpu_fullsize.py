@@ -9,7 +9,7 @@ import torch
 import paper_2502_01776_amd as S
 from oracle import svg_oracle as O
 from workloads import get_config, make_qkv, sample_rows, planted_labels
-from helpers import f64, bits, dev_i32, device_tile_lists, gpu_profile, gpu_layer_kv2, assert_attn_close, labels_match
+from helpers import f64, bits, dev_i32, device_tile_lists, gpu_profile, gpu_layer_kv2, gpu_layer_in_place, assert_attn_close, labels_match
 
 pytestmark = pytest.mark.gpu
 
@@ -51,6 +51,10 @@ def test_full_size_layer_sampled(name):
     o3, kt, vt = gpu_layer_kv2(sh, q, k, v, labels)
     assert torch.equal(o3.view(torch.int16), o.view(torch.int16))
     del o3, kt, vt
+    if sh.block_m == 128:      # and the form without any layout pass (rows gathered by the kernel)
+        o4, guard_ok = gpu_layer_in_place(sh, q, k, v, labels)
+        assert guard_ok and torch.equal(o4.view(torch.int16), o.view(torch.int16))
+        del o4
 
     # profiling: the errors and labels that THIS launch (all heads, all sampled rows, the key-range
     # split and row ordering of the full-size configuration) wrote for one head of each label,

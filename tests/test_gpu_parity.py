@@ -8,7 +8,7 @@ import paper_2502_01776_amd as S
 from oracle import svg_oracle as O
 from workloads import get_config, make_qkv, make_plain_qkv, sample_rows, planted_labels
 from helpers import (f64, bits, dev_i32, device_tile_lists, gpu_profile, gpu_layer, gpu_layer_token_order,
-                     gpu_layer_kv2, assert_attn_close,
+                     gpu_layer_kv2, gpu_layer_in_place, assert_attn_close,
                      labels_match)
 
 pytestmark = pytest.mark.gpu
@@ -309,6 +309,41 @@ def test_layer_with_only_temporal_kv_moved(name, sink):
         S.svg_layout_kv_temporal(sh, kc, vc, kt, kt, labels)           # the two copies overlap
 
 
+@pytest.mark.parametrize("name", ["mid128", "mid64"])
+@pytest.mark.parametrize("sink", [0, 1])
+def test_layer_without_any_layout_pass(name, sink):
+    """SVG_ATTN_QO_TOKEN_ORDER | SVG_ATTN_KV_TOKEN_ORDER: every tensor stays in token order and the
+    kernel gathers the rows of a temporal head's key tiles itself (Sec. 4.3: the transformation fused
+    into the kernel).  Against the oracle, bit-identical to the pipeline with the layout passes, and
+    nothing written past the row table."""
+    cfg, sh, g = setup(name, sink_first_frame=sink)
+    q, k, v = make_qkv(cfg)
+    qc, kc, vc = q.cuda(), k.cuda(), v.cuda()
+    lab_np = planted_labels(cfg)
+    labels = torch.from_numpy(lab_np).cuda()
+    o, guard_ok = gpu_layer_in_place(sh, qc, kc, vc, labels)
+    assert guard_ok
+    ref = O.svg_attention_layer(f64(q), f64(k), f64(v), lab_np.reshape(g.B, g.H), g)
+    for b in range(g.B):
+        for h in range(g.H):
+            assert_attn_close(o[b, h], ref[b, h], f"{name} in-place layer b{b} h{h}")
+    assert torch.equal(o.view(torch.int16), gpu_layer(sh, qc, kc, vc, labels).view(torch.int16))
+    # all heads temporal, all heads spatial
+    for lab in (np.ones_like(lab_np), np.zeros_like(lab_np)):
+        lt = torch.from_numpy(lab).cuda()
+        o1, _ = gpu_layer_in_place(sh, qc, kc, vc, lt)
+        assert torch.equal(o1.view(torch.int16), gpu_layer(sh, qc, kc, vc, lt).view(torch.int16))
+    # workspace too small / missing, and the combinations that do not exist
+    lists = device_tile_lists(sh)
+    nq, nk = S.svg_tile_counts(sh)
+    ws = torch.empty(8 * nk * sh.block_n, dtype=torch.uint8, device="cuda")
+    both = S.SVG_ATTN_QO_TOKEN_ORDER | S.SVG_ATTN_KV_TOKEN_ORDER
+    for kwargs in (dict(flags=both), dict(flags=both, workspace=ws, workspace_bytes=ws.numel() - 4),
+                   dict(flags=both | S.SVG_ATTN_ELEMENT_MASK, workspace=ws, workspace_bytes=ws.numel())):
+        with pytest.raises(S.SvgError):
+            S.svg_sparse_attn_fwd_ex(sh, qc, kc, vc, o, labels, *lists, **kwargs)
+
+
 def test_extended_entry_point_rejects_unknown_flags():
     cfg, sh, g = setup("mid64")
     q, k, v = (x.cuda() for x in make_qkv(cfg))
@@ -407,6 +442,9 @@ def test_random_geometries_whole_layer():
         ref = O.svg_attention_layer(f64(q), f64(k), f64(v), np.array([[0, 1]]), g)
         for h in range(2):
             assert_attn_close(o[0, h], ref[0, h], f"case {case} {cfg} head {h}")
+        if bm == 128:        # the form that gathers k and v rows in the kernel gives the same bits
+            og, guard_ok = gpu_layer_in_place(sh, qc, kc, vc, lab)
+            assert guard_ok and torch.equal(og.view(torch.int16), o.view(torch.int16)), (cfg, case)
         od = torch.zeros_like(qc)
         S.svg_dense_attn_fwd(sh, qc, kc, vc, od)
         torch.cuda.synchronize()
