@@ -79,10 +79,21 @@ const char* svg_last_hip_error(void);
 const char* svg_version(void);
 
 /* Bytes of device workspace svg_profile_heads needs for `t` sampled rows (fp32
- * partial outputs of shape [B,H,t,D] for the spatial pass, the temporal pass and
- * each key range of the unmasked pass, per-row softmax statistics of those ranges,
- * and an int32[t] row order).  0 if shape is invalid. */
+ * partial outputs of shape [B,H,t,D] and per-row softmax statistics for every part
+ * the three passes of Alg. 1 are cut into, see svg_profile_plan, and an int32[t] row
+ * order); also enough for every other call that takes a workspace.  0 if shape is
+ * invalid. */
 size_t svg_workspace_bytes(const svg_shape_t* shape, int32_t t);
+
+/* How svg_profile_heads cuts the passes of Alg. 1 into workgroups for this shape and
+ * t (a pure function of both; host side, nothing is launched).  The unmasked pass of a
+ * group of sampled rows runs as *n_full parts over the key tiles
+ * [full_bound[c], full_bound[c+1]), c < *n_full <= 16 (full_bound: host array of 17
+ * entries, ascending from 0 to nk; may be NULL), each masked pass as *n_masked <= 4
+ * equal parts of its own tile sequence; the parts are merged from per-row (output,
+ * maximum, row sum) triples, so the plan changes the results only in fp32 rounding. */
+int svg_profile_plan(const svg_shape_t* shape, int32_t t, int32_t* n_full, int32_t* n_masked,
+                     int32_t* full_bound);
 
 /* Number of query tiles and key tiles: ceil(N/block_m), ceil(N/block_n). */
 int svg_tile_counts(const svg_shape_t* shape, int32_t* nq, int32_t* nk);

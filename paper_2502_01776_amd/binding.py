@@ -27,7 +27,7 @@ SVG_ATTN_ELEMENT_MASK = 2            # svg_sparse_attn_fwd_ex: the pattern's ele
 SVG_ATTN_KV_TOKEN_ORDER = 4          # svg_sparse_attn_fwd_ex: k, v of temporal heads stay in token order (gathered in the kernel)
 SVG_OK = 0
 
-EXPORTS = ("svg_strerror", "svg_version", "svg_last_hip_error", "svg_workspace_bytes", "svg_tile_counts",
+EXPORTS = ("svg_strerror", "svg_version", "svg_last_hip_error", "svg_workspace_bytes", "svg_profile_plan", "svg_tile_counts",
            "svg_tile_list_build", "svg_profile_heads", "svg_profile_heads_static", "svg_layout_fwd", "svg_layout_inv",
            "svg_sparse_attn_fwd", "svg_sparse_attn_fwd_ex", "svg_dense_attn_fwd",
            "svg_layout_kv_temporal", "svg_sparse_attn_fwd_kv2",
@@ -75,6 +75,8 @@ def lib():
         L.svg_last_hip_error.argtypes = []
         L.svg_workspace_bytes.restype = C.c_size_t
         L.svg_workspace_bytes.argtypes = [sp, C.c_int32]
+        L.svg_profile_plan.restype = C.c_int
+        L.svg_profile_plan.argtypes = [sp, C.c_int32, i32p, i32p, i32p]
         L.svg_tile_counts.restype = C.c_int
         L.svg_tile_counts.argtypes = [sp, i32p, i32p]
         L.svg_tile_list_build.restype = C.c_int
@@ -153,6 +155,14 @@ def svg_version() -> str:
 
 def svg_workspace_bytes(shape: SvgShape, t: int) -> int:
     return int(lib().svg_workspace_bytes(C.byref(shape), int(t)))
+
+
+def svg_profile_plan(shape: SvgShape, t: int):
+    """Returns (n_full, n_masked, full_bound[0 .. n_full])."""
+    nf, nm = C.c_int32(), C.c_int32()
+    bound = (C.c_int32 * 17)()
+    _check(lib().svg_profile_plan(C.byref(shape), int(t), C.byref(nf), C.byref(nm), bound), "svg_profile_plan")
+    return nf.value, nm.value, list(bound)[:nf.value + 1]
 
 
 def svg_tile_counts(shape: SvgShape):

@@ -132,19 +132,20 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
   int bh = 0, grp = 0, variant = 0, chunk = 0;
   if (MODE == kProfile) {
     // (head, row group) pairs are split into 8 contiguous chunks, one per XCD.  Each pair
-    // has nsplit + 2 units of similar length: the unmasked pass cut into nsplit key
-    // ranges, the spatial pass and the temporal pass (both skip most key tiles).  Units
-    // are the outer index inside an XCD's chunk, so neighbouring workgroups stream the
-    // same keys for neighbouring row groups of one head.
+    // has 2 n_masked + n_full units: the parts of the spatial pass, of the temporal pass (both
+    // skip most key tiles) and of the unmasked pass.  Units are the outer index inside an
+    // XCD's chunk, so neighbouring workgroups stream the same keys for neighbouring row
+    // groups of one head.
     const int pairs = a.BH * a.nqt;
     const int pairs_per_xcd = (pairs + 7) >> 3;
     const int unit = loc / pairs_per_xcd;
     const int pair = xcd * pairs_per_xcd + (loc - unit * pairs_per_xcd);
-    if (unit >= a.nsplit + 2 || pair >= pairs) return;
-    // the two masked passes first: their workgroups are the longest ones (mask work on top
-    // of about as many tiles), so they should not be the last to start
-    variant = unit < 2 ? unit + 1 : 0;                       // 0 unmasked, 1 spatial, 2 temporal
-    chunk = unit < 2 ? 0 : unit - 2;
+    const int nm = a.plan.n_masked;
+    if (unit >= a.plan.slots() || pair >= pairs) return;
+    // the masked passes first: their workgroups are the longest ones (mask work on top of
+    // about as many tiles), so they should not be the last to start
+    variant = unit < nm ? 1 : unit < 2 * nm ? 2 : 0;         // 0 unmasked, 1 spatial, 2 temporal
+    chunk = unit < nm ? unit : unit < 2 * nm ? unit - nm : unit - 2 * nm;    // which part of its pass
     bh = pair / a.nqt;
     grp = pair - bh * a.nqt;
   } else if (MODE == kDense) {
@@ -348,9 +349,8 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
   const int c_lo = MODE == kProfile ? wg_range[0] : 0, c_hi = MODE == kProfile ? wg_range[1] : -1;
   int pseg = 0, pj = 0, pjb = -1;
   auto profile_segment = [&](int sidx, int& k0, int& k1) -> bool {   // false: no more segments
-    if (variant == 0) {      // unmasked pass: key tiles [chunk, chunk + 1) * nk / nsplit
-      const int t0 = (int)(((long long)chunk * a.nk) / a.nsplit);
-      const int t1 = (int)(((long long)(chunk + 1) * a.nk) / a.nsplit);
+    if (variant == 0) {      // unmasked pass: the key tiles of part chunk
+      const int t0 = a.plan.full_bound[chunk], t1 = a.plan.full_bound[chunk + 1];
       k0 = t0 * BN;
       k1 = min(a.N, t1 * BN) - 1;
       return sidx == 0;
@@ -382,6 +382,22 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
     }
     return true;
   };
+  int pleft = 0x7fffffff;    // profile: tiles this workgroup may still take
+  // profile: makes [pj, pjb] the next non-empty run of tiles of the pass (intervals may overlap
+  // or touch; a tile is handed out once); false when the pass is exhausted
+  auto profile_interval = [&]() -> bool {
+    while (pj > pjb) {
+      int k0, k1;
+      if (!profile_segment(pseg, k0, k1)) return false;
+      ++pseg;
+      if (k1 < k0) continue;
+      const int ja = k0 / BN, jb = k1 / BN;
+      if (jb < pj) continue;
+      pj = max(pj, ja);
+      pjb = jb;
+    }
+    return true;
+  };
   // The cursor works in two halves.  fetch_begin() at the top of an iteration issues the
   // loads of the next list entries; fetch_end() late in the iteration, where the staged data
   // has just been waited for anyway, turns them into the next entry and advances the
@@ -407,18 +423,28 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
       if (j >= lend) return kNoTile;
       return j;
     }
-    while (pj > pjb) {       // profile: move to the next interval that still has tiles
-      int k0, k1;
-      if (!profile_segment(pseg, k0, k1)) return kNoTile;
-      ++pseg;
-      if (k1 < k0) continue;
-      const int ja = k0 / BN, jb = k1 / BN;
-      if (jb < pj) continue;
-      pj = max(pj, ja);
-      pjb = jb;
-    }
+    if (pleft <= 0) return kNoTile;     // profile
+    if (!profile_interval()) return kNoTile;
+    --pleft;
     return pj++;
   };
+  if (MODE == kProfile && variant != 0 && a.plan.n_masked > 1) {
+    // a masked pass in parts: count the tiles of the whole pass, then take the part's share
+    int total = 0;
+    while (profile_interval()) {
+      total += pjb - pj + 1;
+      pj = pjb + 1;
+    }
+    const int first = (int)(((long long)total * chunk) / a.plan.n_masked);
+    pleft = (int)(((long long)total * (chunk + 1)) / a.plan.n_masked) - first;
+    pseg = 0; pj = 0; pjb = -1;
+    int skip = first;
+    while (skip > 0 && profile_interval()) {
+      const int n = min(skip, pjb - pj + 1);
+      pj += n;
+      skip -= n;
+    }
+  }
   auto next_tile = [&]() -> int {      // both halves at once (prologue)
     fetch_begin();
     return fetch_end();
@@ -842,10 +868,10 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
   const float inv = l_tot > 0.f ? 1.0f / l_tot : 0.f;
   if (MODE == kProfile) {
     if (qslot < a.t) {
-      // output slots: [0, nsplit) unmasked key ranges, nsplit spatial, nsplit + 1 temporal
-      const int slot = variant == 0 ? chunk : a.nsplit + variant - 1;
+      // output slots: the parts of the unmasked pass, of the spatial pass, of the temporal pass
+      const int slot = variant == 0 ? chunk : a.plan.n_full + (variant - 1) * a.plan.n_masked + chunk;
       float* op = static_cast<float*>(a.o) + (((size_t)slot * a.BH + bh) * a.t + qslot) * D;
-      if (variant == 0 && g == 0) a.stats[((size_t)chunk * a.BH + bh) * a.t + qslot] = make_float2(m_run, l_tot);
+      if (g == 0) a.stats[((size_t)slot * a.BH + bh) * a.t + qslot] = make_float2(m_run, l_tot);
 #pragma unroll
       for (int db = 0; db < DB; ++db)
 #pragma unroll
@@ -927,42 +953,57 @@ __global__ __launch_bounds__(1024) void profile_order_kernel(const int32_t* rows
 
 // Squared errors of the two masked outputs against the unmasked one (Alg. 1, last
 // block), first stage: block (x, bh) sums kErrRows sampled rows of head bh and writes
-// one partial pair.  The unmasked output of a row is first reassembled from its nsplit
-// key ranges: each range r holds its normalised output O_r, its reference maximum m_r
-// and its row sum l_r, and O_full = sum_r w_r O_r / sum_r w_r with
-// w_r = l_r * 2^((m_r - max_r m_r) * scale_log2).  Text query rows are skipped (both
-// masks keep every key for them, so they contribute exactly zero).
+// one partial pair.  Each of the three outputs of a row is first reassembled from the
+// parts its pass was cut into: part r holds its normalised output O_r, its reference
+// maximum m_r and its row sum l_r, and O = sum_r w_r O_r / sum_r w_r with
+// w_r = l_r * 2^((m_r - max_r m_r) * scale_log2); a part that kept no key of the row has
+// l_r = 0.  Text query rows are skipped (both masks keep every key for them, so they
+// contribute exactly zero).
 constexpr int kErrRows = 16;
+constexpr int kMaxSlots = kMaxProfileParts + 2 * 4;
 __global__ __launch_bounds__(256) void profile_error_kernel(const float* ws, const float2* stats,
                                                             const int32_t* rows, int BH, int t, int D,
-                                                            int nsplit, float scale_log2, int off,
+                                                            int n_full, int n_masked, float scale_log2, int off,
                                                             int video_end, float2* partial) {
+  // weight[row][slot] = w_r / sum w_r within the slot's pass: one thread per (row, pass)
+  __shared__ float weight[kErrRows][kMaxSlots];
   const int bh = blockIdx.y;
   const size_t per = (size_t)t * D;
-  const float* os = ws + ((size_t)nsplit * BH + bh) * per;
-  const float* ot = ws + ((size_t)(nsplit + 1) * BH + bh) * per;
   const int row0 = blockIdx.x * kErrRows, row1 = min(t, row0 + kErrRows);
+  const int slots = n_full + 2 * n_masked;
+  if (threadIdx.x < kErrRows * 3) {
+    const int rr = threadIdx.x / 3, pass = threadIdx.x % 3, row = row0 + rr;
+    const int slot0 = pass == 0 ? 0 : n_full + (pass - 1) * n_masked, parts = pass == 0 ? n_full : n_masked;
+    if (row < row1) {
+      float m_max = -3.0e38f;
+      for (int r = slot0; r < slot0 + parts; ++r) {
+        const float2 st = stats[((size_t)r * BH + bh) * t + row];
+        if (st.y > 0.f) m_max = fmaxf(m_max, st.x);
+      }
+      float den = 0.f;
+      for (int r = slot0; r < slot0 + parts; ++r) {
+        const float2 st = stats[((size_t)r * BH + bh) * t + row];
+        const float w = st.y > 0.f ? st.y * __builtin_amdgcn_exp2f((st.x - m_max) * scale_log2) : 0.f;
+        weight[rr][r] = w;
+        den += w;
+      }
+      const float inv = den > 0.f ? 1.0f / den : 0.f;
+      for (int r = slot0; r < slot0 + parts; ++r) weight[rr][r] *= inv;
+    }
+  }
+  __syncthreads();
   float acc_s = 0.f, acc_t = 0.f;
   for (size_t e = (size_t)row0 * D + threadIdx.x; e < (size_t)row1 * D; e += 256) {
     const int row = (int)(e / D);
     const int n = rows[row];
     if (n < off || n >= video_end) continue;
-    float m_max = -3.0e38f;
-    for (int r = 0; r < nsplit; ++r) {
-      const float2 st = stats[((size_t)r * BH + bh) * t + row];
-      if (st.y > 0.f) m_max = fmaxf(m_max, st.x);
-    }
-    float num = 0.f, den = 0.f;
-    for (int r = 0; r < nsplit; ++r) {
-      const float2 st = stats[((size_t)r * BH + bh) * t + row];
-      if (st.y > 0.f) {
-        const float w = st.y * __builtin_amdgcn_exp2f((st.x - m_max) * scale_log2);
-        num = __builtin_fmaf(w, ws[((size_t)r * BH + bh) * per + e], num);
-        den += w;
-      }
-    }
-    const float f = den > 0.f ? num / den : 0.f;
-    const float ds = f - os[e], dt = f - ot[e];
+    const float* wr = weight[row - row0];
+    const float* x = ws + (size_t)bh * per + e;       // slot r of this element: x[r * BH * per]
+    float f = 0.f, os = 0.f, ot = 0.f;
+    for (int r = 0; r < n_full; ++r) f = __builtin_fmaf(wr[r], x[(size_t)r * BH * per], f);
+    for (int r = n_full; r < n_full + n_masked; ++r) os = __builtin_fmaf(wr[r], x[(size_t)r * BH * per], os);
+    for (int r = n_full + n_masked; r < slots; ++r) ot = __builtin_fmaf(wr[r], x[(size_t)r * BH * per], ot);
+    const float ds = f - os, dt = f - ot;
     acc_s = __builtin_fmaf(ds, ds, acc_s);
     acc_t = __builtin_fmaf(dt, dt, acc_t);
   }
@@ -1009,7 +1050,7 @@ int launch_one(AttnArgs a, int rows_total, hipStream_t stream) {
   a.total = a.BH * a.nqt;
   const unsigned per_xcd = (unsigned)((a.total + 8 * kCohort - 1) / (8 * kCohort)) * kCohort;   // dense
   if (MODE == kSparse || MODE == kSparseExact || MODE == kSparseGather) a.so = sparse_order(a.BH, a.nqt, BM, a.off, a.video_end, a.N);
-  const unsigned grid = MODE == kProfile ? (unsigned)(8 * (a.nsplit + 2) * ((a.total + 7) / 8))
+  const unsigned grid = MODE == kProfile ? (unsigned)(8 * a.plan.slots() * ((a.total + 7) / 8))
                         : MODE == kDense ? 8u * per_xcd : sparse_grid(a.so, a.BH);
   (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
   hipLaunchKernelGGL((attn_kernel<D, NW, BN, MODE>), dim3(grid), dim3(64 * NW), 0, stream, a);
@@ -1088,14 +1129,14 @@ int launch_profile(const Geo& g, const void* q, const void* k, const void* v, co
   AttnArgs a = base_args(g, q, k, v, workspace);
   a.rows = rows;
   a.t = t;
-  // workspace: fp32 outputs [nsplit + 2][BH][t][D] (unmasked key ranges, spatial,
-  // temporal), range statistics float2 [nsplit][BH][t], partial error sums float2
+  // workspace: fp32 outputs [slots][BH][t][D] (parts of the unmasked, the spatial and the
+  // temporal pass), statistics float2 [slots][BH][t], partial error sums float2
   // [BH][ceil(t/16)], row order int32 [t]
-  const int ns = profile_splits(g);
-  a.nsplit = ns;
+  a.plan = profile_plan(g, t);
+  const int ns = a.plan.slots();
   const int groups = (t + g.bm - 1) / g.bm;
   a.rows_per_group = (t + groups - 1) / groups;
-  const size_t out_floats = (size_t)(ns + 2) * a.BH * t * g.D;
+  const size_t out_floats = (size_t)ns * a.BH * t * g.D;
   float2* stats = reinterpret_cast<float2*>(workspace + out_floats);
   const int n_partial = (t + kErrRows - 1) / kErrRows;
   float2* partial = stats + (size_t)ns * a.BH * t;
@@ -1111,7 +1152,7 @@ int launch_profile(const Geo& g, const void* q, const void* k, const void* v, co
   if (rc != SVG_OK) return rc;
   (void)hipGetLastError();
   hipLaunchKernelGGL(profile_error_kernel, dim3(n_partial, a.BH), dim3(256), 0, stream, workspace, stats,
-                     rows, a.BH, t, g.D, ns, a.scale_log2, g.off, g.video_end, partial);
+                     rows, a.BH, t, g.D, a.plan.n_full, a.plan.n_masked, a.scale_log2, g.off, g.video_end, partial);
   rc = hip_status(hipGetLastError());
   if (rc != SVG_OK) return rc;
   hipLaunchKernelGGL(profile_label_kernel, dim3(a.BH), dim3(64), 0, stream, partial, n_partial, t, g.D,

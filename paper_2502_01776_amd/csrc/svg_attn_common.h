@@ -139,9 +139,9 @@ struct AttnArgs {
   const int32_t* rows;        // profile: sampled rows
   const int32_t* order_t;     // profile: indices into rows[], grouped by in-frame position (temporal variant)
   int t;                      // profile: number of sampled rows
-  int nsplit;                 // profile: key ranges the unmasked pass is cut into
+  ProfilePlan plan;           // profile: parts of the unmasked pass and of the masked passes
   int rows_per_group;         // profile: sampled rows per workgroup (the groups are balanced)
-  float2* stats;              // profile: (reference maximum, row sum) per (key range, head, row)
+  float2* stats;              // profile: (reference maximum, row sum) per (output slot, head, row)
   int N, nk, BH;
   int nqt;                    // workgroups per head: query tiles (dense, sparse) or ceil(t / rows per workgroup) (profile)
   SparseOrder so;             // sparse: which workgroup takes which (head, query tile)

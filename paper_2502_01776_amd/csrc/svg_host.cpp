@@ -4,6 +4,9 @@
 // caller uploads it once per shape.
 #include <algorithm>
 #include <cmath>
+#include <functional>
+#include <mutex>
+#include <queue>
 #include <vector>
 
 #include "svg_internal.h"
@@ -12,6 +15,107 @@ namespace svg {
 
 static thread_local hipError_t g_last_hip_error = hipSuccess;
 void note_hip_error(hipError_t e) { g_last_hip_error = e; }
+
+// ---------------------------------------------------------------------------------------------
+// Plan of the profiling passes (see ProfilePlan).  Cost model, in units of one unmasked key tile:
+// a masked tile costs kMaskedTile (its waves also build and apply element masks, and wait for
+// each other on tiles that only some of them need), every workgroup kStartTiles on top.  The
+// masked passes of a group of rows visit the union of the windows of its rows: the sampled rows
+// are taken to be spread evenly, so a group of a head's rows spans F / groups frames (spatial
+// pass, rows in token order) or P / groups in-frame positions (temporal pass, rows grouped by
+// position).  The workgroups of one XCD are dealt to its kSlots resident places in dispatch
+// order (masked parts first, then the unmasked parts in order) and the plan with the smallest
+// finishing time wins; more parts cost a little extra workspace and merging.
+// ---------------------------------------------------------------------------------------------
+namespace {
+
+constexpr int kSlots = 64;            // workgroups resident on one XCD: 32 CUs x 2
+constexpr double kMaskedTile = 1.5;
+constexpr double kStartTiles = 10.0;
+
+struct PlanKey {
+  int v[12];
+  bool operator==(const PlanKey& o) const { return std::equal(v, v + 12, o.v); }
+};
+
+double finish_time(const std::vector<std::pair<double, int>>& classes) {
+  std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
+  for (int i = 0; i < kSlots; ++i) free_at.push(0.0);
+  double last = 0.0;
+  for (const auto& c : classes)
+    for (int i = 0; i < c.second; ++i) {
+      const double t = free_at.top() + c.first;
+      free_at.pop();
+      free_at.push(t);
+      last = std::max(last, t);
+    }
+  return last;
+}
+
+void fill_bounds(ProfilePlan* p, int n_big, int n_small, int nk) {
+  p->n_full = n_big + n_small;
+  const int total = 2 * n_big + n_small;
+  int cum = 0;
+  for (int c = 0; c <= p->n_full; ++c) {
+    p->full_bound[c] = (int)(((long long)nk * cum) / total);
+    cum += c < n_big ? 2 : 1;
+  }
+  p->full_bound[p->n_full] = nk;
+}
+
+ProfilePlan search_plan(const Geo& g, int t) {
+  const int groups = (t + g.bm - 1) / g.bm;
+  const long long pairs = (long long)g.B * g.H * groups;
+  const int pairs_x = (int)((pairs + 7) / 8);
+  ProfilePlan best = {};
+  best.n_masked = 1;
+  if (g.nk < 4) {                       // a handful of tiles: nothing to cut
+    fill_bounds(&best, 1, 0, g.nk);
+    return best;
+  }
+  if (pairs_x >= 4 * kSlots) {          // many rounds of workgroups anyway: a short tail is all that is needed
+    fill_bounds(&best, 1, 2, g.nk);
+    return best;
+  }
+  const double tile_keys = g.bn;
+  const double len_s = std::min<double>(g.nk, (((double)g.F / groups + 1 + 2 * g.w_s + 1) * g.P + g.T) / tile_keys);
+  const double len_t = std::min<double>(g.nk, ((double)g.F * ((double)g.P / groups + 2 * g.w_t + 1) + g.T) / tile_keys);
+  double best_time = -1.0;
+  for (int nm = 1; nm <= 4; ++nm)
+    for (int n_small = 0; n_small <= 2; n_small += 2)
+      for (int n_big = 1; n_big + n_small <= kMaxProfileParts - 2; ++n_big) {
+        if (2 * n_big + n_small > g.nk) break;
+        std::vector<std::pair<double, int>> classes;
+        classes.emplace_back(len_s * kMaskedTile / nm + kStartTiles, pairs_x * nm);
+        classes.emplace_back(len_t * kMaskedTile / nm + kStartTiles, pairs_x * nm);
+        const double unit = (double)g.nk / (2 * n_big + n_small);
+        classes.emplace_back(2 * unit + kStartTiles, pairs_x * n_big);
+        if (n_small) classes.emplace_back(unit + kStartTiles, pairs_x * n_small);
+        const double time = finish_time(classes) * (1.0 + 0.002 * (n_big + n_small + 2 * nm));
+        if (best_time < 0.0 || time < best_time) {
+          best_time = time;
+          best.n_masked = nm;
+          fill_bounds(&best, n_big, n_small, g.nk);
+        }
+      }
+  return best;
+}
+
+}  // namespace
+
+ProfilePlan profile_plan(const Geo& g, int t) {
+  static std::mutex mu;
+  static std::vector<std::pair<PlanKey, ProfilePlan>> cache;
+  static size_t next = 0;
+  const PlanKey key = {{g.B * g.H, g.F, g.P, g.T, g.text_first, g.w_s, g.w_t, g.bm, g.bn, g.nk, t, 0}};
+  std::lock_guard<std::mutex> lock(mu);
+  for (const auto& e : cache)
+    if (e.first == key) return e.second;
+  const ProfilePlan plan = search_plan(g, t);
+  if (cache.size() < 16) cache.emplace_back(key, plan);
+  else cache[next++ % 16] = std::make_pair(key, plan);
+  return plan;
+}
 
 int make_geo(const svg_shape_t* s, Geo* g) {
   if (!s) return SVG_ERR_INVALID_ARG;
@@ -69,6 +173,20 @@ size_t svg_workspace_bytes(const svg_shape_t* shape, int32_t t) {
   if (svg::make_geo(shape, &g) != SVG_OK || t <= 0) return 0;
   const size_t a = svg::profile_workspace_bytes(g, t), b = svg::row_table_bytes(g);
   return a > b ? a : b;
+}
+
+int svg_profile_plan(const svg_shape_t* shape, int32_t t, int32_t* n_full, int32_t* n_masked,
+                     int32_t* full_bound) {
+  Geo g;
+  int rc = svg::make_geo(shape, &g);
+  if (rc != SVG_OK) return rc;
+  if (t <= 0 || !n_full || !n_masked) return SVG_ERR_INVALID_ARG;
+  const svg::ProfilePlan plan = svg::profile_plan(g, t);
+  *n_full = plan.n_full;
+  *n_masked = plan.n_masked;
+  if (full_bound)
+    for (int c = 0; c <= svg::kMaxProfileParts; ++c) full_bound[c] = plan.full_bound[c < plan.n_full ? c : plan.n_full];
+  return SVG_OK;
 }
 
 int svg_tile_counts(const svg_shape_t* shape, int32_t* nq, int32_t* nk) {

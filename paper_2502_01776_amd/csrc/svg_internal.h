@@ -22,15 +22,28 @@ struct Geo {
 // Checks sizes, D and tile shape.  Returns SVG_OK and fills g, or an error code.
 int make_geo(const svg_shape_t* s, Geo* g);
 
-// Key ranges the unmasked profiling pass is cut into (so that its workgroups are about
-// as long as those of the two masked passes, which skip most key tiles).
-inline int profile_splits(const Geo& g) { return g.nk >= 1024 ? 8 : g.nk >= 32 ? 4 : 1; }
+// How the three passes of online profiling (Alg. 1) are cut into workgroups.  A (head, group of
+// sampled rows) pair has one unmasked pass over all nk key tiles and two masked passes over the
+// tiles their windows can reach; each pass is cut along its tile sequence into parts that run as
+// separate workgroups and are merged afterwards from (output, maximum, row sum) triples.  The
+// unmasked pass has n_full parts with tile boundaries full_bound[] (the last parts may be
+// shorter, so that the workgroups finishing last are short ones), each masked pass n_masked
+// equal parts.  The choice depends on the shape and t only: it minimises the makespan of the
+// workgroups of one XCD under a simple cost model (profile_plan in svg_host.cpp).
+constexpr int kMaxProfileParts = 16;
+struct ProfilePlan {
+  int n_full, n_masked;
+  int full_bound[kMaxProfileParts + 1];
+  __host__ __device__ int slots() const { return n_full + 2 * n_masked; }
+};
+ProfilePlan profile_plan(const Geo& g, int t);
 
-// Bytes of workspace svg_profile_heads uses for t rows.
+// Bytes of workspace svg_profile_heads uses for t rows: fp32 outputs [slots][BH][t][D], float2
+// (maximum, row sum) [slots][BH][t], partial error sums float2 [BH][ceil(t/16)], row order int32 [t].
 inline size_t profile_workspace_bytes(const Geo& g, int t) {
   const size_t bh = (size_t)g.B * g.H;
-  const int ns = profile_splits(g);
-  return (size_t)(ns + 2) * bh * t * g.D * sizeof(float) + (size_t)ns * bh * t * 2 * sizeof(float) +
+  const size_t slots = (size_t)profile_plan(g, t).slots();
+  return slots * bh * t * g.D * sizeof(float) + slots * bh * t * 2 * sizeof(float) +
          bh * (size_t)((t + 15) / 16) * 2 * sizeof(float) + (((size_t)t * 4 + 15) & ~(size_t)15);
 }
 

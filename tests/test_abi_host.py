@@ -230,9 +230,11 @@ def test_pointer_checks_without_gpu():
     assert lkv(k_, v_, v_ + 16, vt_, a, None) == -4
     # workspace
     need = S.svg_workspace_bytes(sh, 24)
-    # one key range for this small shape: 3 outputs + 1 set of row statistics + row order
-    # + partial error sums of 2 row blocks per head
-    assert need == 3 * sh.B * sh.H * 24 * sh.D * 4 + sh.B * sh.H * 24 * 8 + sh.B * sh.H * 2 * 8 + 96
+    # s output slots (the parts the three passes are cut into: at least one each) with one set of row
+    # statistics each, + partial error sums of 2 row blocks per head + row order
+    per_slot = sh.B * sh.H * 24 * (sh.D * 4 + 8)
+    slots, rest = divmod(need - (sh.B * sh.H * 2 * 8 + 96), per_slot)
+    assert rest == 0 and 3 <= slots <= 24
     assert lib.svg_profile_heads(C.byref(sh), a, a, a, a, 24, a, None, None, 0, None) == -3
     assert lib.svg_profile_heads(C.byref(sh), a, a, a, a, 24, a, None, b, need - 1, None) == -3
     assert lib.svg_profile_heads(C.byref(sh), a, a, a, a, 0, a, None, b, need, None) == -1
@@ -240,6 +242,30 @@ def test_pointer_checks_without_gpu():
     # more heads than one grid dimension holds
     many = S.shape_from_config(dict(get_config("mid64"), B=1024, H=64))
     assert lib.svg_profile_heads(C.byref(many), a, a, a, a, 24, a, None, b, 1 << 60, None) == -2
+
+
+def test_profile_plan_is_well_formed_for_every_workload():
+    """The parts the profiling passes are cut into: bounds ascend from 0 to nk, the part counts stay
+    within what the header states, the workspace covers every part, the plan is the same on every
+    call, and bad arguments are refused."""
+    lib = S.lib()
+    for name in ["tiny", "mid64", "mid128", "cogvideox_v1", "wan21_14b", "cogvideox_v15", "hunyuan", "hunyuan_skip85"]:
+        cfg = get_config(name)
+        sh = S.shape_from_config(cfg)
+        nq, nk = S.svg_tile_counts(sh)
+        for t in (1, cfg["t"], 5 * cfg["t"], cfg["N"]):
+            nf, nm, bound = S.svg_profile_plan(sh, t)
+            assert 1 <= nf <= 16 and 1 <= nm <= 4, (name, t, nf, nm)
+            assert bound[0] == 0 and bound[-1] == nk and all(a <= b for a, b in zip(bound, bound[1:])), (name, t, bound)
+            assert (nf, nm, bound) == S.svg_profile_plan(sh, t)
+            BH = cfg["B"] * cfg["H"]
+            want = (nf + 2 * nm) * BH * t * (cfg["D"] * 4 + 8) + BH * (-(-t // 16)) * 8 + ((4 * t + 15) & ~15)
+            assert S.svg_workspace_bytes(sh, t) == max(want, 8 * nk * sh.block_n), (name, t)
+    sh = S.shape_from_config(get_config("mid64"))
+    nf, nm = C.c_int32(), C.c_int32()
+    assert lib.svg_profile_plan(C.byref(sh), 0, C.byref(nf), C.byref(nm), None) == -1
+    assert lib.svg_profile_plan(C.byref(sh), 8, None, C.byref(nm), None) == -1
+    assert lib.svg_profile_plan(C.byref(sh), 8, C.byref(nf), C.byref(nm), None) == 0
 
 
 def test_fp8_buffer_sizes_and_argument_checks_without_gpu():
