@@ -694,7 +694,9 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
     const int tile = col;          // key tile of this iteration
 
     // profile: does this wavefront need the tile at all, and does it need per-element masks?
-    bool skip = false, need_masks = MASKABLE && masked;
+    // (a lane whose row keeps none of the tile's keys while other lanes do needs no element masks
+    // either: it takes its exponentials against +inf, i.e. all weights zero)
+    bool skip = false, need_masks = MASKABLE && masked, drop_lane = false;
     if (MASKABLE && masked) {
       const int cmin = tile_info[buf * 4 + 0], cmax = tile_info[buf * 4 + 1], flags = tile_info[buf * 4 + 2];
       bool lane_all = (flags & 6) == 0, lane_none = (flags & 5) == 0;
@@ -707,7 +709,8 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
         lane_none = lane_none && (cmax < lo || cmin > hi);
       }
       skip = __builtin_amdgcn_ballot_w64(!lane_none) == 0;   // no row of this wave keeps any key
-      need_masks = __builtin_amdgcn_ballot_w64(!lane_all) != 0;
+      need_masks = __builtin_amdgcn_ballot_w64(!lane_all && !lane_none) != 0;   // some row keeps a part of them
+      drop_lane = !need_masks && lane_none;
     }
 
     if (!skip) {
@@ -819,7 +822,7 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
           }
         return l_loc;
       };
-      float l_loc = exponentiate(m_run * a.scale_log2);
+      float l_loc = exponentiate(MASKABLE && drop_lane ? INFINITY : m_run * a.scale_log2);
       if (__builtin_amdgcn_ballot_w64(!(l_loc <= kLazySum)) != 0) {
         float m_loc = sacc[0][0];
 #pragma unroll
@@ -827,6 +830,7 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
 #pragma unroll
           for (int e = 0; e < 16; ++e) m_loc = fmaxf(m_loc, sacc[kb][e]);
         m_loc = both_halves_max(m_loc);
+        if (MASKABLE && drop_lane) m_loc = -INFINITY;
         const float m_new = fmaxf(m_run, m_loc);
         const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * a.scale_log2);
         m_run = m_new;
@@ -835,7 +839,7 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
         for (int db = 0; db < DB; ++db)
 #pragma unroll
           for (int e = 0; e < 16; ++e) oacc[db][e] *= alpha;
-        l_loc = exponentiate(m_new * a.scale_log2);
+        l_loc = exponentiate(MASKABLE && drop_lane ? INFINITY : m_new * a.scale_log2);
       }
       l_run += l_loc;
 
