@@ -403,7 +403,7 @@ def main():
         # algorithmic bytes of profiling: K and V of every head once (the sampled Q rows and the
         # outputs are small); far from the 8 TB/s HBM roof, the stage is MFMA-bound at 1 % of the rows
         "profile_kv_gbs": 2.0 * BH * N * D * 2 / (breakdown["profile"] * 1e-3) / 1e9,
-        "roofline": {"kernel": "attn_kernel<128,4,64,sparse>" if D == 128 else "attn_kernel<64,4,128,sparse>",
+        "roofline": {"kernel": "attn_kernel<128,4,64,sparse>" if D == 128 else "attn_kernel<64,4,64,sparse>",
                      "bound": "mfma", "achieved": achieved, "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                      "frac": achieved / PEAK_BF16_TFLOPS, "traffic": traffic,
                      "traffic_live": False if traffic is not None else None, "counters": counters},
