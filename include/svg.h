@@ -88,9 +88,9 @@ size_t svg_workspace_bytes(const svg_shape_t* shape, int32_t t);
 /* How svg_profile_heads cuts the passes of Alg. 1 into workgroups for this shape and
  * t (a pure function of both; host side, nothing is launched).  The unmasked pass of a
  * group of sampled rows runs as *n_full parts over the key tiles
- * [full_bound[c], full_bound[c+1]), c < *n_full <= 16 (full_bound: host array of 17
+ * [full_bound[c], full_bound[c+1]), c < *n_full (full_bound: host array of 17
  * entries, ascending from 0 to nk; may be NULL), each masked pass as *n_masked <= 4
- * equal parts of its own tile sequence; the parts are merged from per-row (output,
+ * equal parts of its own tile sequence, *n_full <= 6; the parts are merged from per-row (output,
  * maximum, row sum) triples, so the plan changes the results only in fp32 rounding. */
 int svg_profile_plan(const svg_shape_t* shape, int32_t t, int32_t* n_full, int32_t* n_masked,
                      int32_t* full_bound);
@@ -143,7 +143,7 @@ int svg_profile_heads(const svg_shape_t* shape, const void* q, const void* k, co
  * library runs on holds one copy until the process ends).  The call allocates and frees
  * nothing.  A shape and t with svg_workspace_bytes(shape, t) > SVG_STATIC_SCRATCH_BYTES is
  * refused with SVG_ERR_WORKSPACE before anything is enqueued (160 MiB covers every benchmark
- * shape at 1 % sampled rows, the 119k-token one needs 148 MB).  All calls on one GPU share
+ * shape at 1 % sampled rows, the 119k-token one needs 119 MB).  All calls on one GPU share
  * that GPU's array: calls that overlap in time on one GPU (other streams, other threads)
  * race; calls ordered on one stream do not.  Nothing in the array has to be cleared between
  * calls.

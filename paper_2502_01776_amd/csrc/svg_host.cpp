@@ -4,9 +4,6 @@
 // caller uploads it once per shape.
 #include <algorithm>
 #include <cmath>
-#include <functional>
-#include <mutex>
-#include <queue>
 #include <vector>
 
 #include "svg_internal.h"
@@ -17,40 +14,21 @@ static thread_local hipError_t g_last_hip_error = hipSuccess;
 void note_hip_error(hipError_t e) { g_last_hip_error = e; }
 
 // ---------------------------------------------------------------------------------------------
-// Plan of the profiling passes (see ProfilePlan).  Cost model, in units of one unmasked key tile:
-// a masked tile costs kMaskedTile (its waves also build and apply element masks, and wait for
-// each other on tiles that only some of them need), every workgroup kStartTiles on top.  The
-// masked passes of a group of rows visit the union of the windows of its rows: the sampled rows
-// are taken to be spread evenly, so a group of a head's rows spans F / groups frames (spatial
-// pass, rows in token order) or P / groups in-frame positions (temporal pass, rows grouped by
-// position).  The workgroups of one XCD are dealt to its kSlots resident places in dispatch
-// order (masked parts first, then the unmasked parts in order) and the plan with the smallest
-// finishing time wins; more parts cost a little extra workspace and merging.
+// Plan of the profiling passes (see ProfilePlan), from measurements on MI355X with 64 workgroups
+// resident per XCD:
+//  * Unmasked pass: four parts and two of half their length at the end, so that the workgroups
+//    that finish last are short ones (1-3 % less time than eight equal parts; anything from
+//    four to eight parts measured within 1 % of each other).  Fewer parts for short sequences,
+//    and three when the sampled rows alone already give every XCD hundreds of workgroups.
+//  * Masked passes: one part each, unless the (head, row group) pairs are so few that the two
+//    masked workgroups per pair cannot fill an XCD; then as many parts (up to four) as keep
+//    them within its resident places.  CogVideoX-v1 at 1 % (12 pairs per XCD): two parts,
+//    -25 % time; 0.1 % of the rows at the 119k-token shape (3 pairs): four parts, 3.9 -> 1.3 ms;
+//    with 15 or more pairs per XCD any cut of the masked passes measured slower (+4-20 %).
 // ---------------------------------------------------------------------------------------------
 namespace {
 
 constexpr int kSlots = 64;            // workgroups resident on one XCD: 32 CUs x 2
-constexpr double kMaskedTile = 1.5;
-constexpr double kStartTiles = 10.0;
-
-struct PlanKey {
-  int v[12];
-  bool operator==(const PlanKey& o) const { return std::equal(v, v + 12, o.v); }
-};
-
-double finish_time(const std::vector<std::pair<double, int>>& classes) {
-  std::priority_queue<double, std::vector<double>, std::greater<double>> free_at;
-  for (int i = 0; i < kSlots; ++i) free_at.push(0.0);
-  double last = 0.0;
-  for (const auto& c : classes)
-    for (int i = 0; i < c.second; ++i) {
-      const double t = free_at.top() + c.first;
-      free_at.pop();
-      free_at.push(t);
-      last = std::max(last, t);
-    }
-  return last;
-}
 
 void fill_bounds(ProfilePlan* p, int n_big, int n_small, int nk) {
   p->n_full = n_big + n_small;
@@ -63,57 +41,18 @@ void fill_bounds(ProfilePlan* p, int n_big, int n_small, int nk) {
   p->full_bound[p->n_full] = nk;
 }
 
-ProfilePlan search_plan(const Geo& g, int t) {
-  const int groups = (t + g.bm - 1) / g.bm;
-  const long long pairs = (long long)g.B * g.H * groups;
-  const int pairs_x = (int)((pairs + 7) / 8);
-  ProfilePlan best = {};
-  best.n_masked = 1;
-  if (g.nk < 4) {                       // a handful of tiles: nothing to cut
-    fill_bounds(&best, 1, 0, g.nk);
-    return best;
-  }
-  if (pairs_x >= 4 * kSlots) {          // many rounds of workgroups anyway: a short tail is all that is needed
-    fill_bounds(&best, 1, 2, g.nk);
-    return best;
-  }
-  const double tile_keys = g.bn;
-  const double len_s = std::min<double>(g.nk, (((double)g.F / groups + 1 + 2 * g.w_s + 1) * g.P + g.T) / tile_keys);
-  const double len_t = std::min<double>(g.nk, ((double)g.F * ((double)g.P / groups + 2 * g.w_t + 1) + g.T) / tile_keys);
-  double best_time = -1.0;
-  for (int nm = 1; nm <= 4; ++nm)
-    for (int n_small = 0; n_small <= 2; n_small += 2)
-      for (int n_big = 1; n_big + n_small <= kMaxProfileParts - 2; ++n_big) {
-        if (2 * n_big + n_small > g.nk) break;
-        std::vector<std::pair<double, int>> classes;
-        classes.emplace_back(len_s * kMaskedTile / nm + kStartTiles, pairs_x * nm);
-        classes.emplace_back(len_t * kMaskedTile / nm + kStartTiles, pairs_x * nm);
-        const double unit = (double)g.nk / (2 * n_big + n_small);
-        classes.emplace_back(2 * unit + kStartTiles, pairs_x * n_big);
-        if (n_small) classes.emplace_back(unit + kStartTiles, pairs_x * n_small);
-        const double time = finish_time(classes) * (1.0 + 0.002 * (n_big + n_small + 2 * nm));
-        if (best_time < 0.0 || time < best_time) {
-          best_time = time;
-          best.n_masked = nm;
-          fill_bounds(&best, n_big, n_small, g.nk);
-        }
-      }
-  return best;
-}
-
 }  // namespace
 
 ProfilePlan profile_plan(const Geo& g, int t) {
-  static std::mutex mu;
-  static std::vector<std::pair<PlanKey, ProfilePlan>> cache;
-  static size_t next = 0;
-  const PlanKey key = {{g.B * g.H, g.F, g.P, g.T, g.text_first, g.w_s, g.w_t, g.bm, g.bn, g.nk, t, 0}};
-  std::lock_guard<std::mutex> lock(mu);
-  for (const auto& e : cache)
-    if (e.first == key) return e.second;
-  const ProfilePlan plan = search_plan(g, t);
-  if (cache.size() < 16) cache.emplace_back(key, plan);
-  else cache[next++ % 16] = std::make_pair(key, plan);
+  const int groups = (t + g.bm - 1) / g.bm;
+  const long long pairs = (long long)g.B * g.H * groups;
+  const long long pairs_x = (pairs + 7) / 8;
+  ProfilePlan plan = {};
+  plan.n_masked = (int)std::max<long long>(1, std::min<long long>(4, (kSlots - 8) / (2 * pairs_x)));
+  if (g.nk < 24) fill_bounds(&plan, 1, 0, g.nk);
+  else if (pairs_x >= 4 * kSlots) fill_bounds(&plan, 1, 2, g.nk);
+  else if (g.nk < 96) fill_bounds(&plan, 2, 2, g.nk);
+  else fill_bounds(&plan, 4, 2, g.nk);
   return plan;
 }
 

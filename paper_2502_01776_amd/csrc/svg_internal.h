@@ -26,10 +26,9 @@ int make_geo(const svg_shape_t* s, Geo* g);
 // sampled rows) pair has one unmasked pass over all nk key tiles and two masked passes over the
 // tiles their windows can reach; each pass is cut along its tile sequence into parts that run as
 // separate workgroups and are merged afterwards from (output, maximum, row sum) triples.  The
-// unmasked pass has n_full parts with tile boundaries full_bound[] (the last parts may be
-// shorter, so that the workgroups finishing last are short ones), each masked pass n_masked
-// equal parts.  The choice depends on the shape and t only: it minimises the makespan of the
-// workgroups of one XCD under a simple cost model (profile_plan in svg_host.cpp).
+// unmasked pass has n_full <= 6 parts with tile boundaries full_bound[] (the last parts are
+// shorter, so that the workgroups finishing last are short ones), each masked pass n_masked <= 4
+// equal parts.  The choice depends on the shape and t only (profile_plan in svg_host.cpp).
 constexpr int kMaxProfileParts = 16;
 struct ProfilePlan {
   int n_full, n_masked;

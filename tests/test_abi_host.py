@@ -234,7 +234,7 @@ def test_pointer_checks_without_gpu():
     # statistics each, + partial error sums of 2 row blocks per head + row order
     per_slot = sh.B * sh.H * 24 * (sh.D * 4 + 8)
     slots, rest = divmod(need - (sh.B * sh.H * 2 * 8 + 96), per_slot)
-    assert rest == 0 and 3 <= slots <= 24
+    assert rest == 0 and 3 <= slots <= 14
     assert lib.svg_profile_heads(C.byref(sh), a, a, a, a, 24, a, None, None, 0, None) == -3
     assert lib.svg_profile_heads(C.byref(sh), a, a, a, a, 24, a, None, b, need - 1, None) == -3
     assert lib.svg_profile_heads(C.byref(sh), a, a, a, a, 0, a, None, b, need, None) == -1
@@ -255,7 +255,7 @@ def test_profile_plan_is_well_formed_for_every_workload():
         nq, nk = S.svg_tile_counts(sh)
         for t in (1, cfg["t"], 5 * cfg["t"], cfg["N"]):
             nf, nm, bound = S.svg_profile_plan(sh, t)
-            assert 1 <= nf <= 16 and 1 <= nm <= 4, (name, t, nf, nm)
+            assert 1 <= nf <= 6 and 1 <= nm <= 4, (name, t, nf, nm)
             assert bound[0] == 0 and bound[-1] == nk and all(a <= b for a, b in zip(bound, bound[1:])), (name, t, bound)
             assert (nf, nm, bound) == S.svg_profile_plan(sh, t)
             BH = cfg["B"] * cfg["H"]
