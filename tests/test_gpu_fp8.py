@@ -108,6 +108,25 @@ def test_fp8_layer_against_the_oracle(sink):
     assert rel < 0.15
 
 
+@pytest.mark.parametrize("heads", [5, 64, 67])
+def test_fp8_every_head_is_computed_for_any_head_count(heads):
+    """Same dispatch order as the bf16 kernel: random labels, more heads than the 64 a label ballot
+    covers; every output row finite, two heads against the oracle."""
+    cfg, sh, g = setup("mid128", H=heads, spatial_heads=[])
+    q, k, v = make_qkv(cfg)
+    rng = np.random.default_rng(heads)
+    lab_np = rng.integers(0, 2, size=heads).astype(np.uint8)
+    labels = torch.from_numpy(lab_np).cuda()
+    o = gpu_layer_fp8(sh, q.cuda(), k.cuda(), v.cuda(), labels)
+    assert torch.isfinite(o.float()).all()
+    vmax = float(np.abs(f64(v)).max())
+    g1 = O.Geometry(**{**g.__dict__, "H": 1})
+    for h in (0, heads - 1):
+        ref = O.svg_attention_layer_fp8(f64(q[:, h:h + 1]), f64(k[:, h:h + 1]), f64(v[:, h:h + 1]),
+                                        lab_np[h:h + 1].reshape(1, 1), g1)
+        assert_fp8_attn_close(o[0, h], ref[0, 0], vmax, f"fp8 H={heads} head {h}")
+
+
 def test_fp8_without_labels_uses_the_spatial_list_in_token_order():
     cfg, sh, g = setup("mid128")
     q, k, v = make_qkv(cfg)

@@ -344,6 +344,40 @@ def test_layer_without_any_layout_pass(name, sink):
             S.svg_sparse_attn_fwd_ex(sh, qc, kc, vc, o, labels, *lists, **kwargs)
 
 
+@pytest.mark.parametrize("heads, label_kind", [(1, "mixed"), (3, "temporal"), (7, "mixed"), (64, "mixed"), (64, "spatial"),
+                                                (65, "mixed"), (70, "temporal"), (130, "mixed")])
+def test_every_head_and_query_tile_is_computed_for_any_head_count_and_label_mix(heads, label_kind):
+    """The dispatch order of the sparse passes (text-row query tiles first, then an eighth of each
+    label's tile sequence per XCD; label classes taken from a 64-lane ballot, more than 64 heads in head
+    order) must hand out every (head, query tile) exactly once whatever the head count and the labels
+    are: the output buffer starts as NaN and every row of every head is compared with the oracle for
+    four heads and must be finite and equal to the token-order form for all."""
+    cfg, sh, g = setup("mid128", H=heads, spatial_heads=[])
+    q, k, v = make_plain_qkv(1, heads, g.N, g.D, seed=77 + heads)
+    qc, kc, vc = q.cuda(), k.cuda(), v.cuda()
+    rng = np.random.default_rng(heads)
+    lab_np = {"mixed": rng.integers(0, 2, size=heads), "temporal": np.ones(heads), "spatial": np.zeros(heads)}[label_kind].astype(np.uint8)
+    labels = torch.from_numpy(lab_np).cuda()
+    lists = device_tile_lists(sh)
+    kp, vp = torch.empty_like(kc), torch.empty_like(vc)
+    S.svg_layout_fwd(sh, kc, kp, labels)
+    S.svg_layout_fwd(sh, vc, vp, labels)
+    o = torch.full_like(qc, float("nan"))
+    S.svg_sparse_attn_fwd_ex(sh, qc, kp, vp, o, labels, *lists, flags=S.SVG_ATTN_QO_TOKEN_ORDER)
+    torch.cuda.synchronize()
+    assert torch.isfinite(o.float()).all(), "some (head, query tile) was never written"
+    for h in sorted({0, heads // 2, heads - 1, int(rng.integers(heads))}):
+        ref = O.svg_attention_layer(f64(q[:, h:h + 1]), f64(k[:, h:h + 1]), f64(v[:, h:h + 1]),
+                                    lab_np[h:h + 1].reshape(1, 1), O.Geometry(**{**g.__dict__, "H": 1}))
+        assert_attn_close(o[0, h], ref[0, 0], f"H={heads} {label_kind} head {h}")
+    # the other forms hand out the same work
+    og, guard_ok = gpu_layer_in_place(sh, qc, kc, vc, labels, lists)
+    assert guard_ok and torch.isfinite(og.float()).all()
+    assert torch.equal(og.view(torch.int16), o.view(torch.int16))
+    o4 = gpu_layer(sh, qc, kc, vc, labels, lists)
+    assert torch.equal(o4.view(torch.int16), o.view(torch.int16))
+
+
 def test_extended_entry_point_rejects_unknown_flags():
     cfg, sh, g = setup("mid64")
     q, k, v = (x.cuda() for x in make_qkv(cfg))
