@@ -579,6 +579,24 @@ def main():
             "extra_device_memory_bytes": 8 * nk * cfg["block_n"],
             "extra_device_memory_bytes_with_layout_pass": 2 * q.numel() * 2}
         del o_g
+    if folded and not in_kernel:
+        # the same pass under the exact element masks of Sec. 3.1 instead of their block cover
+        o_e = torch.empty_like(o)
+        for _ in range(2):
+            S.svg_sparse_attn_fwd_kv2(sh, q, k, v, kp, vp, o_e, labels, *lists, flags=S.SVG_ATTN_ELEMENT_MASK)
+        torch.cuda.synchronize()
+        times = []
+        for _ in range(args.steps):
+            e0, e1 = ev(), ev()
+            e0.record()
+            S.svg_sparse_attn_fwd_kv2(sh, q, k, v, kp, vp, o_e, labels, *lists, flags=S.SVG_ATTN_ELEMENT_MASK)
+            e1.record()
+            torch.cuda.synchronize()
+            times.append(e0.elapsed_time(e1))
+        out["exact_element_mask"] = {
+            "sparse_attn_ms": float(np.median(times)), "block_form_ms": breakdown["sparse_attn"],
+            "relative_rms_difference_to_block_form": float((o_e.float() - o.float()).norm() / o.float().norm())}
+        del o_e
     if args.without_layout_transform:
         # same labels, same kernel, unpermuted q, k, v: the temporal slot gets the list of the
         # temporal mask in frame-major order
