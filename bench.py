@@ -188,20 +188,21 @@ def cpu_baseline(cfg, q, k, v, rows, labels_np, nnz_total, o_bf16=None, o_fp8=No
     return out
 
 
-def measured_matrix_peak(S, torch, ms_target=12.0):
+def measured_matrix_peak(S, torch, head_dim, ms_target=12.0):
     """Sustained rate of the bf16 matrix cores on this machine: a loop of products only (form 0) and
-    the same loop with the per-product LDS read and softmax instructions of the D = 128 attention
-    kernel (form 1), on normally distributed operands, each timed over >= 10 ms; and the
+    the same loop with the per-product LDS read and softmax instructions of the attention kernel
+    of this head dimension (form 1: D = 128, form 2: D = 64, twice the softmax instructions per
+    product and three workgroups per CU), on normally distributed operands, each timed over >= 10 ms; and the
     product-only loop on all-zero operands, which shows how much of the published peak is lost to
     the power the data toggling draws (the clock drops under real data, not under zeros)."""
     gen = torch.Generator(device="cuda").manual_seed(11)
     operands = torch.randn(1 << 19, generator=gen, device="cuda").to(torch.bfloat16)      # 1 MiB
-    wgs = 2048
+    wgs = 3072         # a multiple of the 512 and of the 768 workgroups the chip holds in forms 0/1 and 2
     sink = torch.empty(wgs * 256, dtype=torch.float32, device="cuda")
     out = {}
     zeros = torch.zeros_like(operands)
     for form, key, ops in ((0, "products_only", operands),
-                           (1, "with_lds_operand_reads_and_softmax_instructions", operands),
+                           (1 if head_dim == 128 else 2, "with_lds_operand_reads_and_softmax_instructions", operands),
                            (0, "products_only_constant_operands", zeros)):
         iters = 500
         for attempt in range(3):
@@ -373,7 +374,7 @@ def main():
     # algorithmic bytes of the layout stage: one read and one write of every tensor row that has to move
     # (temporal heads only); the four-pass form also copies the spatial heads, which is not counted
     layout_bytes = 2.0 * n_temporal * N * D * 2
-    peak_live = None if args.no_measured_peak else measured_matrix_peak(S, torch)
+    peak_live = None if args.no_measured_peak else measured_matrix_peak(S, torch, D)
     out = {
         "metric": "effective TFLOP/s of one sparse attention layer at %dk tokens "
                   "(4*N^2*D*H / ms per layer; profile + layout + block-sparse attention + inverse layout%s)"

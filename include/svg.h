@@ -322,13 +322,16 @@ int svg_sparse_attn_fp8_fwd(const svg_shape_t* shape, const void* q8, const void
  * Measurement aid, not a step of the method: the rate the bf16 matrix cores sustain on this
  * GPU, which the roofline of the attention kernels (Sec. 5.3: kernel-level efficiency) is
  * read against besides the published peak.  Launches `workgroups` workgroups of 4
- * wavefronts (two resident per compute unit), each wavefront issuing 16 * iterations
+ * wavefronts (two resident per compute unit, three in form 2), each wavefront issuing 16 * iterations
  * products v_mfma_f32_32x32x16_bf16 on operands taken from `operands`.
  *   form 0   products only, operands in registers
  *   form 1   per product additionally one 1 KB operand read from LDS and the softmax
  *            instructions the D = 128 attention kernel spends per product (one FMA, one
  *            exponential, one addition, half a bf16 pack): an upper bound for that kernel
  *            design, without its staging, barriers and global memory traffic
+ *   form 2   the same for the D = 64 kernel: three workgroups resident per compute unit, and
+ *            per product the softmax instructions of two scores per lane (two FMAs, two
+ *            exponentials, one bf16 pack, one packed dot product)
  *   operands device, 1 MiB, 16-byte aligned: bf16 values (random data draws the power real
  *            data draws; zeros would let the clock rise)
  *   sink     device float [workgroups * 256], written (keeps the products alive)

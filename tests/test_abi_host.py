@@ -312,7 +312,7 @@ def test_rate_probe_argument_checks_without_gpu():
     lib = S.lib()
     a = 0x10000000
     flop = C.c_double()
-    assert lib.svg_probe_mfma_bf16(2, 8, 1, a, a, C.byref(flop), None) == -1        # unknown form
+    assert lib.svg_probe_mfma_bf16(3, 8, 1, a, a, C.byref(flop), None) == -1        # unknown form
     assert lib.svg_probe_mfma_bf16(0, 0, 1, a, a, C.byref(flop), None) == -1
     assert lib.svg_probe_mfma_bf16(0, 8, 0, a, a, C.byref(flop), None) == -1
     assert lib.svg_probe_mfma_bf16(0, 8, 1, None, a, C.byref(flop), None) == -1

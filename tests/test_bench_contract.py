@@ -45,7 +45,7 @@ def test_matrix_core_rate_probe_runs_and_counts_its_work():
     import paper_2502_01776_amd as S
     ops = torch.randn(1 << 19, device="cuda").to(torch.bfloat16)
     sink = torch.zeros(64 * 256, dtype=torch.float32, device="cuda")
-    for form in (0, 1):
+    for form in (0, 1, 2):
         flop = S.svg_probe_mfma_bf16(form, 64, 10, ops, sink)
         torch.cuda.synchronize()
         assert flop == 64 * 4 * 10 * 16 * 2.0 * 32 * 32 * 16
