@@ -75,7 +75,7 @@ constexpr int waves_per_simd(int D, int NW, int MODE) {
   return NW != 4 ? 1 : (D == 64 && (MODE == kDense || MODE == kSparse || MODE == kSparseGather)) ? 3 : 2;
 }
 
-template <int D, int NW, int BN, int MODE>
+template <int D, int NW, int BN, int MODE, int LW>
 __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_kernel(AttnArgs a) {
   constexpr int BM = 32 * NW;            // query rows per workgroup = rows of a query tile
   constexpr int THREADS = 64 * NW;
@@ -162,7 +162,7 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
   // sparse: heavy tiles first, then an eighth of each label's sequence of tiles
   int pat = 0, cl = -1, head_cl0 = 0;
   if (SPARSE) {
-    if (!sparse_slot(a.so, a.BH, a.labels, a.row_ptr[0], a.row_ptr[1], bh, grp, pat, cl, head_cl0)) return;
+    if (!sparse_slot<LW>(a.so, a.BH, a.labels, a.row_ptr[0], a.row_ptr[1], bh, grp, pat, cl, head_cl0)) return;
     bh = __builtin_amdgcn_readfirstlane(bh);
     grp = __builtin_amdgcn_readfirstlane(grp);
     pat = __builtin_amdgcn_readfirstlane(pat);
@@ -1057,7 +1057,11 @@ int launch_one(AttnArgs a, int rows_total, hipStream_t stream) {
   const unsigned grid = MODE == kProfile ? (unsigned)(8 * a.plan.slots() * ((a.total + 7) / 8))
                         : MODE == kDense ? 8u * per_xcd : sparse_grid(a.so, a.BH);
   (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process
-  hipLaunchKernelGGL((attn_kernel<D, NW, BN, MODE>), dim3(grid), dim3(64 * NW), 0, stream, a);
+  constexpr bool SPARSE_MODE = MODE == kSparse || MODE == kSparseExact || MODE == kSparseGather;
+  if (SPARSE_MODE && a.BH > 64)      // label classes over more than one 64-head word
+    hipLaunchKernelGGL((attn_kernel<D, NW, BN, MODE, SPARSE_MODE ? kWideLabelWords : 1>), dim3(grid), dim3(64 * NW), 0, stream, a);
+  else
+    hipLaunchKernelGGL((attn_kernel<D, NW, BN, MODE, 1>), dim3(grid), dim3(64 * NW), 0, stream, a);
   return hip_status(hipGetLastError());
 }
 

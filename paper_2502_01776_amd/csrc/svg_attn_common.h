@@ -38,8 +38,10 @@ constexpr float kLazySum = 8192.0f;      // a lane's per-tile sum of exponential
 //    and one of the temporal sequence, the one with the longer lists first.  Each XCD so gets
 //    the same share of both kinds of work whatever the labels are, and consecutive workgroups
 //    of an XCD still are neighbouring query tiles of one head (overlapping key windows).
-// With more than 64 heads the labels are not looked at: one sequence in head order.
+// With more than 256 heads the labels are not looked at: one sequence in head order.
 // --------------------------------------------------------------------------------------------
+constexpr int kWideLabelWords = 4;     // label classes are formed for up to 64 * kWideLabelWords heads
+
 struct SparseOrder {
   int g_lo;    // a head's query tiles without a text row are [g_lo, g_lo + nl)
   int nl;
@@ -67,14 +69,30 @@ inline unsigned sparse_grid(const SparseOrder& so, int BH) {
 // Which (head, query tile, pattern) does this workgroup take?  false: none.  For a tile without
 // text rows, cl is its index in its label's sequence and head_cl0 the index of its head's first
 // tile there (cl = -1 for a heavy tile).  Every value returned is the same in all lanes.
+// (LW: 64-head words of label bits; the kernels are built for 1 and for kWideLabelWords, and the
+// launcher takes the wide form only when there are more than 64 heads)
+template <int LW>
 __device__ __forceinline__ bool sparse_slot(const SparseOrder so, const int BH, const uint8_t* labels,
                                             const int32_t* rp_s, const int32_t* rp_t, int& bh, int& grp,
                                             int& pat, int& cl, int& head_cl0) {
   const int xcd = blockIdx.x & 7, loc = blockIdx.x >> 3;
   const int lane = threadIdx.x & 63;
-  const bool classed = labels != nullptr && BH <= 64;
-  unsigned long long m = 0;       // bit h: head h is temporal
-  if (classed) m = __builtin_amdgcn_ballot_w64(lane < BH && labels[lane < BH ? lane : 0] != 0);
+  // the labels as bit masks, 64 heads per word (bit = temporal)
+  const bool classed = labels != nullptr && BH <= 64 * LW;
+  unsigned long long m[LW];
+  int nT = 0;
+#pragma unroll
+  for (int w = 0; w < LW; ++w) {
+    const int h = 64 * w + lane;
+    m[w] = classed && 64 * w < BH ? __builtin_amdgcn_ballot_w64(h < BH && labels[h < BH ? h : 0] != 0) : 0ull;
+    nT += __builtin_popcountll(m[w]);
+  }
+  auto label_bit = [&](int h) -> int {
+    unsigned long long word = m[0];
+#pragma unroll
+    for (int w = 1; w < LW; ++w) word = (h >> 6) == w ? m[w] : word;
+    return (int)((word >> (h & 63)) & 1);
+  };
   cl = -1;
   head_cl0 = 0;
   if (loc < so.hmax) {
@@ -82,12 +100,12 @@ __device__ __forceinline__ bool sparse_slot(const SparseOrder so, const int BH, 
     bh = xcd + 8 * hh;
     if (bh >= BH) return false;
     grp = j < so.g_lo ? j : j + so.nl;
-    pat = classed ? (int)((m >> bh) & 1) : (labels ? labels[bh] != 0 : 0);
+    pat = classed ? label_bit(bh) : (labels ? labels[bh] != 0 : 0);
     return true;
   }
   if (so.nl == 0) return false;
   int l = loc - so.hmax;
-  const int nT = __builtin_popcountll(m), nS = BH - nT;
+  const int nS = BH - nT;
   int first = nS == 0;            // the label whose sequence comes first
   if (nT > 0 && nS > 0) {
     const int nnz_s = rp_s[so.g_lo + so.nl] - rp_s[so.g_lo];
@@ -111,12 +129,24 @@ __device__ __forceinline__ bool sparse_slot(const SparseOrder so, const int BH, 
   head_cl0 = kth * so.nl;
   grp = so.g_lo + (cl - head_cl0);
   if (classed) {
-    // the kth head (from 0) with label c
-    const unsigned long long valid = BH == 64 ? ~0ull : (1ull << BH) - 1;
-    const unsigned long long cm = c ? m : ~m & valid;
-    const int rank = __builtin_popcountll(cm & ((1ull << lane) - 1));
-    const unsigned long long hit = __builtin_amdgcn_ballot_w64(((cm >> lane) & 1) != 0 && rank == kth);
-    bh = __builtin_ctzll(hit);
+    // the kth head (from 0) with label c: find its word, then its bit
+    bh = 0;
+    int before = 0;
+    bool found = false;
+#pragma unroll
+    for (int w = 0; w < LW; ++w) {
+      const int left = BH - 64 * w;
+      const unsigned long long valid = left >= 64 ? ~0ull : left > 0 ? (1ull << left) - 1 : 0ull;
+      const unsigned long long cm = c ? m[w] : ~m[w] & valid;
+      const int cnt = __builtin_popcountll(cm);
+      if (!found && kth < before + cnt) {
+        const int rank = __builtin_popcountll(cm & ((1ull << lane) - 1));
+        const unsigned long long hit = __builtin_amdgcn_ballot_w64(((cm >> lane) & 1) != 0 && rank == kth - before);
+        bh = 64 * w + __builtin_ctzll(hit);
+        found = true;
+      }
+      before += cnt;
+    }
     pat = c;
   } else {
     bh = kth;

@@ -202,13 +202,14 @@ struct Fp8Args {
   int off, video_end, F, P, sink, w_s, w_t;
 };
 
+template <int LW>
 __global__ __launch_bounds__(256, 2) void attn_fp8_kernel(Fp8Args a) {
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * kStageBytes];
 
   // heavy query tiles first, then an eighth of each label's sequence of tiles (the same
   // dispatch order as the bf16 kernel)
   int bh = 0, grp = 0, pat = 0, cl = -1, head_cl0 = 0;
-  if (!sparse_slot(a.so, a.BH, a.labels, a.row_ptr[0], a.row_ptr[1], bh, grp, pat, cl, head_cl0)) return;
+  if (!sparse_slot<LW>(a.so, a.BH, a.labels, a.row_ptr[0], a.row_ptr[1], bh, grp, pat, cl, head_cl0)) return;
   bh = __builtin_amdgcn_readfirstlane(bh);
   grp = __builtin_amdgcn_readfirstlane(grp);
   pat = __builtin_amdgcn_readfirstlane(pat);
@@ -514,7 +515,8 @@ int launch_fp8_attention(const Geo& g, const void* q8, const void* k8, const voi
   a.w_s = g.w_s; a.w_t = g.w_t;
   const unsigned grid = sparse_grid(a.so, a.BH);
   (void)hipGetLastError();
-  hipLaunchKernelGGL(attn_fp8_kernel, dim3(grid), dim3(256), 0, stream, a);
+  if (a.BH > 64) hipLaunchKernelGGL(attn_fp8_kernel<kWideLabelWords>, dim3(grid), dim3(256), 0, stream, a);
+  else hipLaunchKernelGGL(attn_fp8_kernel<1>, dim3(grid), dim3(256), 0, stream, a);
   return hip_status(hipGetLastError());
 }
 

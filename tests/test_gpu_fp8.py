@@ -108,7 +108,7 @@ def test_fp8_layer_against_the_oracle(sink):
     assert rel < 0.15
 
 
-@pytest.mark.parametrize("heads", [5, 64, 67])
+@pytest.mark.parametrize("heads", [5, 64, 67, 258])
 def test_fp8_every_head_is_computed_for_any_head_count(heads):
     """Same dispatch order as the bf16 kernel: random labels, more heads than the 64 a label ballot
     covers; every output row finite, two heads against the oracle."""

@@ -345,7 +345,7 @@ def test_layer_without_any_layout_pass(name, sink):
 
 
 @pytest.mark.parametrize("heads, label_kind", [(1, "mixed"), (3, "temporal"), (7, "mixed"), (64, "mixed"), (64, "spatial"),
-                                                (65, "mixed"), (70, "temporal"), (130, "mixed")])
+                                                (65, "mixed"), (70, "temporal"), (130, "mixed"), (256, "mixed"), (260, "mixed")])
 def test_every_head_and_query_tile_is_computed_for_any_head_count_and_label_mix(heads, label_kind):
     """The dispatch order of the sparse passes (text-row query tiles first, then an eighth of each
     label's tile sequence per XCD; label classes taken from a 64-lane ballot, more than 64 heads in head
