@@ -62,7 +62,7 @@ constexpr int kNoTile = 0x7fffffff;
 // wavefronts sharing a SIMD then settle into opposite phases: the products of one run
 // back to back while the other's softmax and staging instructions fill the gaps.
 constexpr int kPrioProducts = 1;
-constexpr int kCohort = 64;   // consecutive query tiles that share an XCD (and its L2) at a time
+constexpr int kCohort = 64;   // dense: consecutive query tiles that share an XCD (and its L2) at a time
 constexpr int kPrefetch = 4;          // LDS operand reads kept in flight ahead of the products
 constexpr unsigned kRsrcFlags = 0x00020000u;   // raw buffer, 32-bit data format (gfx9 encoding)
 
@@ -166,8 +166,6 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
     bh = __builtin_amdgcn_readfirstlane(bh);
     grp = __builtin_amdgcn_readfirstlane(grp);
     pat = __builtin_amdgcn_readfirstlane(pat);
-    cl = __builtin_amdgcn_readfirstlane(cl);
-    head_cl0 = __builtin_amdgcn_readfirstlane(head_cl0);
   }
 
   // profile: the unmasked pass needs no key codes, tile summaries or element masks (only the
@@ -284,65 +282,13 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
     lend = __builtin_amdgcn_readfirstlane(rp[grp + 1]);
     lj = lbeg;
     lleft = lend - lbeg;
-    // Where to start in the (cyclically walked) list.  Neighbouring query tiles run at the
-    // same time on one XCD and their key windows overlap but are shifted against each other;
-    // walked from their own first tile they would ask L2 for different tiles at every
-    // moment.  Instead all query tiles of a cohort (cs consecutive ones of a head) start at
-    // one common key tile, the first window tile of the cohort member with the highest
-    // window, wrap around at the end of their list and stop where they started: as long
-    // as they run at the same pace they all want the same K/V tile at the same time.  The
-    // order of the tiles does not change the result beyond fp32 summation order, and a
-    // full list (every member starts at tile 0) is walked exactly like the dense kernel.
-    //   How many query tiles form a cohort follows from the geometry: the key window of the
-    // pattern, counted in list tiles, against the shift between neighbouring query tiles; the
-    // largest power of two (up to kCohort) for which the anchor still lies inside the window
-    // of every member.  Short windows (a few dozen tiles) get no common start at all: their
-    // workgroups live too briefly to spend memory round trips on finding one.
-    const int win_tiles = (int)min((pat ? (2LL * a.w_t + 1) * a.F : (2LL * a.w_s + 1) * a.P) / BN, 1LL << 20);
-    int cs = kCohort;
-    while (cs > 1 && (cs - 1) * (BM / BN) >= win_tiles) cs >>= 1;
-    if (lleft > 1 && cl >= 0 && cs >= 8) {
-      const int first_video_tile = (a.off + BN - 1) / BN;      // tiles before it are text-prefix tiles
-      // cohort: the tiles of the same aligned block of cs in the label's sequence, as far as they
-      // belong to this head (none of them holds a text row; a tile that does starts at the
-      // beginning of its list, which is every key tile).  Member with the highest window: the
-      // last query tile of the cohort.
-      const int top = a.so.g_lo + min(cl | (cs - 1), head_cl0 + a.so.nl - 1) - head_cl0;
-      // own first and last entry: a list is one run of consecutive tiles (the window) with the
-      // text tiles in front of or behind it, so the place of a tile inside it can usually be
-      // told from one of its ends without searching (every load saved here is a memory
-      // round trip in front of the first K/V tile)
-      const int c_first = cols[lbeg], c_last = cols[lend - 1];
-      // the top member's first entry that is no text-prefix tile, among the first eight (loaded together)
-      const int tb = rp[top], te = rp[top + 1];
-      int cand[8];
-#pragma unroll
-      for (int j = 0; j < 8; ++j) cand[j] = cols[min(tb + j, te - 1)];
-      int anchor = -1;
-#pragma unroll
-      for (int j = 7; j >= 0; --j)
-        if (tb + j < te && cand[j] >= first_video_tile) anchor = cand[j];
-      if (anchor >= c_first && anchor <= c_last) {
-        // own entry == anchor: counted from the front, from the back, else by binary search
-        const int from_front = anchor - c_first, from_back = (lleft - 1) - (c_last - anchor);
-        const bool front_ok = from_front < lleft, back_ok = from_back >= 0;
-        const int at_front = cols[lbeg + (front_ok ? from_front : 0)];
-        const int at_back = cols[lbeg + (back_ok ? from_back : 0)];
-        if (front_ok && at_front == anchor) {
-          lj = lbeg + from_front;
-        } else if (back_ok && at_back == anchor) {
-          lj = lbeg + from_back;
-        } else {
-          int lo = 0, hi = lleft;
-          while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (cols[lbeg + mid] < anchor) lo = mid + 1; else hi = mid;
-          }
-          if (lo < lleft && cols[lbeg + lo] == anchor) lj = lbeg + lo;
-        }
-      }
-      lj = __builtin_amdgcn_readfirstlane(lj);     // (uniform by construction: keeps the cursor scalar)
-    }
+    // The list is walked from its first entry.  Neighbouring query tiles run at the same time on
+    // one XCD with key windows shifted by BM / BN tiles against each other, so each finds in L2
+    // what its neighbour fetched a moment ago.  (An earlier form started all query tiles of a
+    // cohort of up to 64 at one common key tile and walked the lists cyclically; with whole heads
+    // dealt to the XCDs that saved a third of the traffic past L2, with the dispatch order used
+    // now it cost 1-2 % time and nearly doubled that traffic: 47.9 against 27.5 GB per launch at
+    // the 119k-token shape.)
   } else if (MODE == kDense) {
     lend = a.nk;
   }
@@ -415,7 +361,7 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
       if (lleft <= 0) return kNoTile;
       const int c = __builtin_amdgcn_readfirstlane(pend0);
       --lleft;
-      if (++lj >= lend) lj = lbeg;
+      ++lj;
       return c;
     }
     if (MODE == kDense) {
