@@ -484,11 +484,11 @@ def main():
         freq = 1.0 / 10000.0 ** (torch.arange(D // 2, device="cuda", dtype=torch.float32) / (D // 2))
         theta = torch.arange(nv, device="cuda", dtype=torch.float32)[:, None] * freq[None, :]
         cos_t, sin_t = torch.cos(theta).contiguous(), torch.sin(theta).contiguous()
-        yq = qp        # scratch outputs (the timed pipeline is over)
+        yq = qp        # scratch outputs: qp and op (kp and vp still hold the copies later comparisons read)
 
         def fused():
             S.svg_qk_norm_rope(sh, q, yq, norm, wgt, bia, 1e-6, cos_t, sin_t, S.SVG_ROPE_INTERLEAVED)
-            S.svg_qk_norm_rope(sh, k, kp, norm, wgt, bia, 1e-6, cos_t, sin_t, S.SVG_ROPE_INTERLEAVED)
+            S.svg_qk_norm_rope(sh, k, op, norm, wgt, bia, 1e-6, cos_t, sin_t, S.SVG_ROPE_INTERLEAVED)
 
         off = cfg["T"] if cfg["text_first"] else 0
 
