@@ -999,7 +999,7 @@ int launch_one(AttnArgs a, int rows_total, hipStream_t stream) {
   a.nqt = (rows_total + BM - 1) / BM;
   a.total = a.BH * a.nqt;
   const unsigned per_xcd = (unsigned)((a.total + 8 * kCohort - 1) / (8 * kCohort)) * kCohort;   // dense
-  if (MODE == kSparse || MODE == kSparseExact || MODE == kSparseGather) a.so = sparse_order(a.BH, a.nqt, BM, a.off, a.video_end, a.N);
+  if (MODE == kSparse || MODE == kSparseExact || MODE == kSparseGather) a.so = sparse_order(a.BH, a.nqt, BM, a.off, a.video_end, a.N, 32 * (NW == 4 ? waves_per_simd(D, NW, MODE) : 2));
   const unsigned grid = MODE == kProfile ? (unsigned)(8 * a.plan.slots() * ((a.total + 7) / 8))
                         : MODE == kDense ? 8u * per_xcd : sparse_grid(a.so, a.BH);
   (void)hipGetLastError();   // drop any stale error left by earlier runtime calls of the process

@@ -37,7 +37,15 @@ constexpr float kLazySum = 8192.0f;      // a lane's per-tile sum of exponential
 //    ascending query tiles); every XCD takes one contiguous eighth of the spatial sequence
 //    and one of the temporal sequence, the one with the longer lists first.  Each XCD so gets
 //    the same share of both kinds of work whatever the labels are, and consecutive workgroups
-//    of an XCD still are neighbouring query tiles of one head (overlapping key windows).
+//    of an XCD still are nearby query tiles of one head (overlapping key windows).
+//  * Inside the part of a head that an XCD takes, the query tiles are dispatched with a stride:
+//    0, r, 2r, ..., then 1, r+1, ...  A workgroup walks its list one key tile per tile time, the
+//    window of query tile g + 1 lies BM / BN = 2 key tiles above that of g, and in steady state
+//    a place on the XCD frees up every T / slots tile times (T: tiles per list, slots: resident
+//    workgroups).  With r = T / (2 slots) the next workgroup starts exactly as much later as
+//    its window lies higher, so all workgroups of the XCD read the same key tile at the same
+//    time and L2 serves all but one of them.  r is rounded, at least 1, per label (the lists of
+//    the two patterns differ in length).
 // With more than 256 heads the labels are not looked at: one sequence in head order.
 // --------------------------------------------------------------------------------------------
 constexpr int kWideLabelWords = 4;     // label classes are formed for up to 64 * kWideLabelWords heads
@@ -47,9 +55,10 @@ struct SparseOrder {
   int nl;
   int nh;      // tiles with a text row per head (the others, ascending)
   int hmax;    // workgroups per XCD reserved for them
+  int slots;   // workgroups resident on one XCD (sets the stride, see above)
 };
 
-inline SparseOrder sparse_order(int BH, int nqt, int BM, int off, int video_end, int N) {
+inline SparseOrder sparse_order(int BH, int nqt, int BM, int off, int video_end, int N, int slots) {
   SparseOrder so;
   const int lo = off > 0 ? (off + BM - 1) / BM : 0;
   int hi = video_end < N ? video_end / BM : nqt;
@@ -58,6 +67,7 @@ inline SparseOrder sparse_order(int BH, int nqt, int BM, int off, int video_end,
   so.nl = hi - so.g_lo;
   so.nh = nqt - so.nl;
   so.hmax = so.nh * ((BH + 7) / 8);
+  so.slots = slots;
   return so;
 }
 
@@ -107,11 +117,9 @@ __device__ __forceinline__ bool sparse_slot(const SparseOrder so, const int BH, 
   int l = loc - so.hmax;
   const int nS = BH - nT;
   int first = nS == 0;            // the label whose sequence comes first
-  if (nT > 0 && nS > 0) {
-    const int nnz_s = rp_s[so.g_lo + so.nl] - rp_s[so.g_lo];
-    const int nnz_t = rp_t[so.g_lo + so.nl] - rp_t[so.g_lo];
-    first = nnz_t > nnz_s;
-  }
+  const int nnz_s = nS > 0 ? rp_s[so.g_lo + so.nl] - rp_s[so.g_lo] : 0;      // list tiles of a head's light query tiles
+  const int nnz_t = nT > 0 ? rp_t[so.g_lo + so.nl] - rp_t[so.g_lo] : 0;
+  if (nT > 0 && nS > 0) first = nnz_t > nnz_s;
   const int nA = first ? nT : nS;
   const long long NA = (long long)nA * so.nl, NB = (long long)(BH - nA) * so.nl;
   const int a0 = (int)((xcd * NA) >> 3), a1 = (int)(((xcd + 1) * NA) >> 3);
@@ -127,6 +135,25 @@ __device__ __forceinline__ bool sparse_slot(const SparseOrder so, const int BH, 
   }
   const int kth = cl / so.nl;
   head_cl0 = kth * so.nl;
+  {
+    // strided order inside the part [s0, s1) of this head that lies in the XCD's chunk
+    const int c0 = c == first ? a0 : b0, c1 = c == first ? a1 : b1;
+    const int s0 = max(c0, head_cl0), s1 = min(c1, head_cl0 + so.nl);
+    const int len = s1 - s0;
+    const int tiles_per_list = (c ? nnz_t : nnz_s) / so.nl;
+    const int r = min(16, (tiles_per_list + so.slots) / (2 * so.slots));      // round(T / (2 slots))
+    int idx = cl - s0;
+    if (r > 1 && len > r) {
+      int p = 0;
+      for (; p < r; ++p) {        // which pass (p, p + r, p + 2r, ...) the idx-th workgroup belongs to
+        const int in_pass = (len - p + r - 1) / r;
+        if (idx < in_pass) break;
+        idx -= in_pass;
+      }
+      idx = p + idx * r;
+    }
+    cl = s0 + idx;
+  }
   grp = so.g_lo + (cl - head_cl0);
   if (classed) {
     // the kth head (from 0) with label c: find its word, then its bit

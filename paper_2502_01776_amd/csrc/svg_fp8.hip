@@ -509,7 +509,9 @@ int launch_fp8_attention(const Geo& g, const void* q8, const void* k8, const voi
   a.row_ptr[1] = row_ptr_t; a.col_idx[1] = col_idx_t;
   a.N = g.N; a.nk = g.nk; a.BH = g.B * g.H;
   a.nqt = g.nq;
-  a.so = sparse_order(a.BH, a.nqt, kBM, g.off, g.video_end, g.N);
+  // (no stride in the dispatch order: this kernel starts the query tiles of a cohort at a common key tile
+  // instead, which measured 0.6-1.8 % faster here than the stride with or without that start)
+  a.so = sparse_order(a.BH, a.nqt, kBM, g.off, g.video_end, g.N, 1 << 24);
   a.scale_log2 = g.scale * 1.4426950408889634f;
   a.off = g.off; a.video_end = g.video_end; a.F = g.F; a.P = g.P; a.sink = g.sink;
   a.w_s = g.w_s; a.w_t = g.w_t;
