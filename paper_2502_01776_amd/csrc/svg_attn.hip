@@ -12,15 +12,17 @@
 // exchange between lane l and lane l+32, the rescale factor is one scalar per lane,
 // and the exponentiated S^T registers are, after bf16 packing, exactly the B operand
 // of the second product: register pair (2kk, 2kk+1) of a 32-key block holds keys
-// {16kk+4g+j} and {16kk+8+4g+j}, j<4, g = lane/32, and the V^T operand is stored
-// for the same key order, so P never moves between lanes or through LDS.
+// {16kk+4g+j} and {16kk+8+4g+j}, j<4, g = lane/32, and the V^T operand is read in
+// the same key order, so P never moves between lanes or through LDS.
 //
 // Staging: K and V tiles go global -> registers (raw buffer loads, bounds-checked
-// descriptors, loop-invariant offsets) -> LDS, double buffered, with the loads of
-// tile j+1 in flight while tile j is computed and one barrier per tile.  K rows are
-// padded by 16 bytes (conflict-free ds_read_b128 of the A operand with compile-time
-// offsets); V is transposed in registers on the way in (v_perm_b32) so that one
-// ds_read_b128 is a whole A operand of the second product.  Operand reads run a few
+// descriptors, loop-invariant offsets) -> LDS as straight 16-byte copies, double
+// buffered, with the loads of tile j+1 in flight while tile j is computed and one
+// barrier per tile.  K rows are padded by 16 bytes (conflict-free ds_read_b128 of the A
+// operand with compile-time offsets).  V stays row-major too: the transposing LDS read
+// of gfx950 (ds_read_b64_tr_b16) hands a lane the same channel of four consecutive
+// keys, so two of them are a whole A operand of the second product and nothing is
+// transposed in registers.  Operand reads run a few
 // products ahead of their use (rolling window), including the first V^T operands,
 // which are requested before the softmax starts.
 //
@@ -90,31 +92,28 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
   constexpr bool MASKABLE = MODE == kProfile || MODE == kSparseExact;
   constexpr int DS = D / 16;             // k-steps of the first product
   constexpr int DB = D / 32;             // 32-row blocks of O^T
-  constexpr int K_PIECES = BN * CPR;
-  constexpr int V_UNITS = (BN / 8) * CPR;   // a unit = 8 keys x 8 channels
-  // Staging work: with 4 wavefronts every thread stages K_PER_THREAD 16-byte pieces of K and half
-  // a V unit (4 row loads, a register transpose of 4 keys x 8 channels, 8-byte LDS writes), so
-  // that all wavefronts reach the barrier with the same amount of work behind them; a single
-  // wavefront stages whole V units.
-  constexpr bool SPLIT = NW == 4;
-  constexpr int V_HALVES = 2 * V_UNITS;
-  constexpr int K_PER_THREAD = (K_PIECES + THREADS - 1) / THREADS;
-  constexpr int V_PER_THREAD = SPLIT ? 1 : (V_UNITS + THREADS - 1) / THREADS;
+  constexpr int PIECES = BN * CPR;       // 16-byte pieces of a K tile, and of a V tile
+  // Staging work: thread tid copies the pieces tid + i * THREADS of K and of V, global -> registers
+  // -> LDS, so all wavefronts reach the barrier with the same amount of work behind them.
+  constexpr int PER_THREAD = PIECES / THREADS;
+  static_assert(PIECES % THREADS == 0 && THREADS % CPR == 0 && (THREADS / CPR) % 4 == 0,
+                "a thread's pieces must lie a multiple of four rows apart");
   // K staging: row-major, rows padded by 16 bytes so that the 16 lanes served together
   // by a ds_read_b128 of the A operand (16 consecutive keys, same channel piece) fall on
   // different banks, while every operand address stays base + compile-time offset.
   constexpr int K_ROW = D * 2 + 16;
   constexpr int K_BYTES = BN * K_ROW;
-  // V^T staging: [8-key group][d][8 keys], 16 bytes per (group, d): one ds_read_b128
-  // is a whole A operand of the second product.  Group (kb, kk, g) holds the keys
-  // 32 kb + 16 kk + 4 g + {0..3, 8..11}, i.e. the k-slots of half-wave g.  Inside a
-  // group the 16-byte slot of channel d = 8 c + dd is 8 c + (dd ^ (c & 7)), which
-  // makes both the transposing writes and the operand reads conflict-free.
-  constexpr int V_ROW = D * 16;
-  constexpr int V_BYTES = (BN / 8) * V_ROW;
+  // V staging: row-major as well, not transposed.  The A operand of the second product is V^T,
+  // which the transposing LDS read of gfx950 (ds_read_b64_tr_b16) delivers directly: the 16
+  // lanes of a quarter wavefront read 4 rows x 16 channels (lane s: 8 bytes of row s / 4 at
+  // channel 4 (s % 4)) and lane i receives channel i of the four rows.  Two such reads (rows
+  // 4 g + {0..3} and 8 + 4 g + {0..3} of a 16-key step) are one operand in the key order the
+  // weights are held in.  The 32-byte slots of a row are XOR-swizzled with the row's two low bits
+  // (v_swizzle), which puts the four rows of a quarter wavefront, and the eight row pieces of a
+  // half wavefront, on different banks; rows stay unpadded.
+  constexpr int V_ROW = D * 2;
+  constexpr int V_BYTES = BN * V_ROW;
   constexpr int STAGE_BYTES = K_BYTES + V_BYTES;
-  static_assert(!SPLIT || (V_HALVES % 64 == 0 && V_HALVES <= THREADS), "V staging must be done by whole wavefronts");
-  static_assert(!SPLIT || (K_PIECES % THREADS == 0 && THREADS % CPR == 0), "K staging threads must cover whole rows");
 
   __shared__ __attribute__((aligned(16))) unsigned char lds[2 * STAGE_BYTES];
   __shared__ __attribute__((aligned(16))) int key_code[MASKABLE ? 2 * BN : 4];
@@ -399,22 +398,18 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
   // ======================================================================================
   // Staging of one K/V tile.
   // ======================================================================================
-  u32x4 kst[K_PER_THREAD];               // K pieces
-  u32x4 vst[V_PER_THREAD][SPLIT ? 4 : 8];   // rows of a V unit (four wavefronts: of half a unit)
-  // which wavefronts stage V at all (whole wavefronts; read through readfirstlane so that the
-  // branch is scalar)
-  const bool v_role = !SPLIT || __builtin_amdgcn_readfirstlane(tid >> 6) < V_HALVES / 64;
-
-  // row of the e-th key of V group kg8 = (kb, kk, g):  32 kb + 16 kk + 4 g + e (+4 if e >= 4)
-  auto v_key = [](int kg8, int e) { return (kg8 >> 1) * 16 + (kg8 & 1) * 4 + e + (e >= 4 ? 4 : 0); };
+  u32x4 kst[PER_THREAD], vst[PER_THREAD];     // this thread's pieces of K and of V
 
   // The descriptor of a tile starts at the tile's first key row and covers the rows up to
   // N, so the per-thread offsets are loop invariant, no clamping arithmetic is needed, and
-  // rows beyond N (ragged last tile) read as zero.
-  // four wavefronts: thread tid stages the K pieces tid + i * THREADS, and keys 4 h .. 4 h + 3 of the
-  // V unit tid / 2 with h = tid % 2 (the two threads of a unit write the two halves of its slots)
-  const int k_stage_off = SPLIT ? ((tid / CPR) * D + (tid % CPR) * 8) * 2 : 0;
-  const int v_stage_off = SPLIT ? (v_key((tid >> 1) / CPR, 4 * (tid & 1)) * D + ((tid >> 1) % CPR) * 8) * 2 : 0;
+  // rows beyond N (ragged last tile) read as zero.  Piece tid + i * THREADS is piece tid % CPR of
+  // row tid / CPR + i * (THREADS / CPR).
+  const int stage_row = tid / CPR, stage_piece = tid % CPR;
+  const int stage_off = (stage_row * D + stage_piece * 8) * 2;
+  // 32-byte slot s of V row n sits at slot s ^ v_swizzle(n) of the row in LDS
+  auto v_swizzle = [](int n) { const int j = n & 3; return D == 128 ? (2 * j) ^ (j >> 1) : j; };
+  const int k_lds_off = stage_row * K_ROW + (stage_piece << 4);
+  const int v_lds_off = stage_row * V_ROW + (((stage_piece >> 1) ^ v_swizzle(stage_row)) << 5) + ((stage_piece & 1) << 4);
 
   // Gathering form: every K/V row is fetched through a table of source rows.  For a temporal
   // head row v of the P-outer order is token row_table[entries + v] (Sec. 4.2; text rows map to
@@ -423,19 +418,14 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
   // loads return as zero.  The entries of a tile are loaded one tile ahead of its K/V rows; a
   // row is 2 D contiguous bytes, so the loads stay whole cache lines.
   const int tab_base = GATHER && pat != 0 ? a.nk * BN * 4 : 0;
-  int tabk[GATHER ? K_PER_THREAD : 1];
-  i32x4 tabv = {0, 0, 0, 0};
+  int tab[GATHER ? PER_THREAD : 1];
   auto load_table = [&](int col_any) {
     const int key0 = __builtin_amdgcn_readfirstlane(col_any) * BN;
     const __amdgpu_buffer_rsrc_t rt = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<int32_t*>(a.row_table), 0, 2u * (unsigned)a.nk * BN * 4u, kRsrcFlags);
 #pragma unroll
-    for (int i = 0; i < K_PER_THREAD; ++i)
-      tabk[i] = __builtin_amdgcn_raw_buffer_load_b32(rt, (tid / CPR + i * (THREADS / CPR)) * 4, tab_base + key0 * 4, 0);
-    if (v_role) {
-      const u32x4 tv = __builtin_amdgcn_raw_buffer_load_b128(rt, v_key((tid >> 1) / CPR, 4 * (tid & 1)) * 4, tab_base + key0 * 4, 0);
-      tabv = i32x4{(int)tv[0], (int)tv[1], (int)tv[2], (int)tv[3]};
-    }
+    for (int i = 0; i < PER_THREAD; ++i)
+      tab[i] = __builtin_amdgcn_raw_buffer_load_b32(rt, (stage_row + i * (THREADS / CPR)) * 4, tab_base + key0 * 4, 0);
   };
 
   auto load_tile = [&](int col_any) {
@@ -443,15 +433,12 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
       const unsigned head_bytes = (unsigned)a.N * (D * 2);
       const __amdgpu_buffer_rsrc_t rk = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(kh), 0, head_bytes, kRsrcFlags);
       const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(const_cast<__bf16*>(vh), 0, head_bytes, kRsrcFlags);
-      const int piece_k = (tid % CPR) * 16, piece_v = ((tid >> 1) % CPR) * 16;
 #pragma unroll
-      for (int i = 0; i < K_PER_THREAD; ++i)
-        kst[i] = __builtin_amdgcn_raw_buffer_load_b128(rk, tabk[i] * (D * 2) + piece_k, 0, 0);
-      if (v_role) {
+      for (int i = 0; i < PER_THREAD; ++i)
+        kst[i] = __builtin_amdgcn_raw_buffer_load_b128(rk, tab[i] * (D * 2) + stage_piece * 16, 0, 0);
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-          vst[0][e] = __builtin_amdgcn_raw_buffer_load_b128(rv, tabv[e] * (D * 2) + piece_v, 0, 0);
-      }
+      for (int i = 0; i < PER_THREAD; ++i)
+        vst[i] = __builtin_amdgcn_raw_buffer_load_b128(rv, tab[i] * (D * 2) + stage_piece * 16, 0, 0);
       return;
     }
     // the tile index is the same in every lane; saying so keeps the descriptors scalar
@@ -461,84 +448,23 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
         const_cast<__bf16*>(kh + (size_t)key0 * D), 0, bytes_left, kRsrcFlags);
     const __amdgpu_buffer_rsrc_t rv = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<__bf16*>(vh + (size_t)key0 * D), 0, bytes_left, kRsrcFlags);
-    if (SPLIT) {
 #pragma unroll
-      for (int i = 0; i < K_PER_THREAD; ++i)    // piece tid + i * THREADS: THREADS / CPR rows further on
-        kst[i] = __builtin_amdgcn_raw_buffer_load_b128(rk, k_stage_off + i * (THREADS / CPR) * (D * 2), 0, 0);
-      if (v_role) {
+    for (int i = 0; i < PER_THREAD; ++i)
+      kst[i] = __builtin_amdgcn_raw_buffer_load_b128(rk, stage_off + i * (THREADS / CPR) * (D * 2), 0, 0);
 #pragma unroll
-        for (int e = 0; e < 4; ++e)              // four consecutive rows
-          vst[0][e] = __builtin_amdgcn_raw_buffer_load_b128(rv, v_stage_off + e * (D * 2), 0, 0);
-      }
-    } else {
-#pragma unroll
-      for (int i = 0; i < K_PER_THREAD; ++i) {
-        const int u = tid + i * THREADS;
-        kst[i] = __builtin_amdgcn_raw_buffer_load_b128(rk, ((u / CPR) * D + (u % CPR) * 8) * 2, 0, 0);
-      }
-#pragma unroll
-      for (int i = 0; i < V_PER_THREAD; ++i) {
-        const int u = tid + i * THREADS;
-        if (V_UNITS % THREADS == 0 || u < V_UNITS) {
-#pragma unroll
-          for (int e = 0; e < 8; ++e)
-            vst[i][e] = __builtin_amdgcn_raw_buffer_load_b128(rv, (v_key(u / CPR, e) * D + (u % CPR) * 8) * 2, 0, 0);
-        }
-      }
-    }
-  };
-
-  // 8 keys x 8 channels (rows[e][w] = channels 2w, 2w+1 of key e) -> LDS as 8 channels x 8 keys
-  auto store_v_unit = [&](unsigned char* vb, int kg8, int c, const u32x4* rows) {
-    unsigned char* dst = vb + kg8 * V_ROW + c * 128;
-    const int sw = c & 7;
-#pragma unroll
-    for (int dd = 0; dd < 8; ++dd) {
-      const unsigned sel = (dd & 1) ? 0x07060302u : 0x05040100u;
-      u32x4 o;
-#pragma unroll
-      for (int kp = 0; kp < 4; ++kp)
-        o[kp] = __builtin_amdgcn_perm(rows[2 * kp + 1][dd >> 1], rows[2 * kp][dd >> 1], sel);
-      *reinterpret_cast<u32x4*>(dst + ((dd ^ sw) << 4)) = o;
-    }
-  };
-
-  // 4 keys x 8 channels -> the 8-byte half h of the unit's eight 16-byte slots
-  auto store_v_half = [&](unsigned char* vb, int kg8, int c, int h, const u32x4* rows) {
-    unsigned char* dst = vb + kg8 * V_ROW + c * 128 + h * 8;
-    const int sw = c & 7;
-#pragma unroll
-    for (int dd = 0; dd < 8; ++dd) {
-      const unsigned sel = (dd & 1) ? 0x07060302u : 0x05040100u;
-      u32x2 o;
-      o[0] = __builtin_amdgcn_perm(rows[1][dd >> 1], rows[0][dd >> 1], sel);
-      o[1] = __builtin_amdgcn_perm(rows[3][dd >> 1], rows[2][dd >> 1], sel);
-      *reinterpret_cast<u32x2*>(dst + ((dd ^ sw) << 4)) = o;
-    }
+    for (int i = 0; i < PER_THREAD; ++i)
+      vst[i] = __builtin_amdgcn_raw_buffer_load_b128(rv, stage_off + i * (THREADS / CPR) * (D * 2), 0, 0);
   };
 
   auto store_tile = [&](int buf, int col) {
     unsigned char* kb = lds + buf * STAGE_BYTES;
     unsigned char* vb = kb + K_BYTES;
-    if (SPLIT) {
 #pragma unroll
-      for (int i = 0; i < K_PER_THREAD; ++i) {
-        const int u = tid + i * THREADS;
-        *reinterpret_cast<u32x4*>(kb + (u / CPR) * K_ROW + ((u % CPR) << 4)) = kst[i];
-      }
-      if (v_role) store_v_half(vb, (tid >> 1) / CPR, (tid >> 1) % CPR, tid & 1, vst[0]);
-    } else {
+    for (int i = 0; i < PER_THREAD; ++i)
+      *reinterpret_cast<u32x4*>(kb + k_lds_off + i * (THREADS / CPR) * K_ROW) = kst[i];
 #pragma unroll
-      for (int i = 0; i < K_PER_THREAD; ++i) {
-        const int u = tid + i * THREADS;
-        *reinterpret_cast<u32x4*>(kb + (u / CPR) * K_ROW + ((u % CPR) << 4)) = kst[i];
-      }
-#pragma unroll
-      for (int i = 0; i < V_PER_THREAD; ++i) {
-        const int u = tid + i * THREADS;
-        if (V_UNITS % THREADS == 0 || u < V_UNITS) store_v_unit(vb, u / CPR, u % CPR, vst[i]);
-      }
-    }
+    for (int i = 0; i < PER_THREAD; ++i)     // rows a multiple of four apart: the same swizzle
+      *reinterpret_cast<u32x4*>(vb + v_lds_off + i * (THREADS / CPR) * V_ROW) = vst[i];
     if (MASKABLE && masked && tid < BN) {
       // per-key mask code: the key's frame (spatial) or in-frame position (temporal), or
       // "kept by every query" (text / sink key, unmasked pass), or "out of range"
@@ -620,13 +546,15 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
   for (int s = 0; s < DS; ++s) asm volatile("" ::"v"(qreg[s]));
 
   int buf = 0;
-  // byte offset of channel d = 32 db + r inside a V^T group row (see store_v_unit)
+  // V^T operand reads: this lane's source address inside a 16-key step for channel block db.  As
+  // a source lane of the transposing read, lane 16 q + s of the wavefront (q = 2 g + h) supplies
+  // the 8 bytes of row 4 g + s / 4 at channel 32 db + 16 h + 4 (s % 4).
   int v_off[DB];
+  {
+    const int s = lane & 15, j = s >> 2, h = (lane >> 4) & 1;
 #pragma unroll
-  for (int db = 0; db < DB; ++db) {
-    const int d = db * 32 + r;
-    const int c = d >> 3, dd = d & 7;
-    v_off[db] = c * 128 + ((dd ^ (c & 7)) << 4);
+    for (int db = 0; db < DB; ++db)
+      v_off[db] = (4 * g + j) * V_ROW + (((2 * db + h) ^ v_swizzle(j)) << 5) + ((s & 3) << 3);
   }
   const bool ragged = (a.N % BN) != 0;
 
@@ -674,8 +602,11 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
         return *reinterpret_cast<const bf16x8*>(kbuf + (kb * 32 + r) * K_ROW + ((2 * s + g) << 4));
       };
       auto v_operand = [&](int i) -> bf16x8 {
-        const int kg8 = (i / DB) * 2 + g, db = i % DB;     // i / DB = kb * 2 + kk
-        return *reinterpret_cast<const bf16x8*>(vbuf + kg8 * V_ROW + v_off[db]);
+        const int step = i / DB, db = i % DB;     // step = kb * 2 + kk: rows 16 step .. 16 step + 15
+        const unsigned char* src = vbuf + step * 16 * V_ROW + v_off[db];
+        const i16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)src);
+        const i16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4*)(src + 8 * V_ROW));
+        return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
       };
       f32x16 sacc[KB];
       bf16x8 opnd[PF];
