@@ -66,8 +66,8 @@ constexpr int kNoTile = 0x7fffffff;
 constexpr int kPrioProducts = 1;
 constexpr int kCohort = 64;   // dense: consecutive query tiles that share an XCD (and its L2) at a time
 // LDS operand reads kept in flight ahead of the products: eight where the registers allow it
-// (head dimension 128 without the mask state; 0.3 % over four), four elsewhere
-constexpr int prefetch_depth(int D, int NW, bool maskable) { return D == 128 && NW == 4 && !maskable ? 8 : 4; }
+// (the dense and the plain sparse pass at head dimension 128; 0.3 % over four), four elsewhere
+constexpr int prefetch_depth(int D, int NW, int MODE) { return D == 128 && NW == 4 && (MODE == kDense || MODE == kSparse) ? 8 : 4; }
 constexpr unsigned kRsrcFlags = 0x00020000u;   // raw buffer, 32-bit data format (gfx9 encoding)
 
 // Wavefronts per SIMD the register budget is set for.  Head dimension 128 fills 256 registers
@@ -95,11 +95,10 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
   constexpr int DS = D / 16;             // k-steps of the first product
   constexpr int DB = D / 32;             // 32-row blocks of O^T
   constexpr int PIECES = BN * CPR;       // 16-byte pieces of a K tile, and of a V tile
-  // Staging work: thread tid copies the pieces tid + i * THREADS of K and of V, global -> registers
-  // -> LDS, so all wavefronts reach the barrier with the same amount of work behind them.
+  // Staging work: every thread copies PER_THREAD pieces of K and of V, global -> registers -> LDS,
+  // so all wavefronts reach the barrier with the same amount of work behind them.
   constexpr int PER_THREAD = PIECES / THREADS;
-  static_assert(PIECES % THREADS == 0 && THREADS % CPR == 0 && (THREADS / CPR) % 4 == 0,
-                "a thread's pieces must lie a multiple of four rows apart");
+  static_assert(PIECES % THREADS == 0 && THREADS % CPR == 0, "every thread stages the same piece of whole rows");
   // K staging: row-major, rows padded by 16 bytes so that the 16 lanes served together
   // by a ds_read_b128 of the A operand (16 consecutive keys, same channel piece) fall on
   // different banks, while every operand address stays base + compile-time offset.
@@ -404,14 +403,20 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
 
   // The descriptor of a tile starts at the tile's first key row and covers the rows up to
   // N, so the per-thread offsets are loop invariant, no clamping arithmetic is needed, and
-  // rows beyond N (ragged last tile) read as zero.  Piece tid + i * THREADS is piece tid % CPR of
-  // row tid / CPR + i * (THREADS / CPR).
-  const int stage_row = tid / CPR, stage_piece = tid % CPR;
+  // rows beyond N (ragged last tile) read as zero.  A thread stages piece tid % CPR of PER_THREAD
+  // rows: rows tid / CPR + i (THREADS / CPR), so that a wavefront's load covers consecutive rows,
+  // or, in the gathering form, where the rows come from anywhere, the consecutive rows
+  // PER_THREAD (tid / CPR) + i, whose row numbers one load fetches.
+  constexpr int ROW_STEP = GATHER ? 1 : THREADS / CPR;
+  const int stage_row = (tid / CPR) * (GATHER ? PER_THREAD : 1), stage_piece = tid % CPR;
   const int stage_off = (stage_row * D + stage_piece * 8) * 2;
   // 32-byte slot s of V row n sits at slot s ^ v_swizzle(n) of the row in LDS
   auto v_swizzle = [](int n) { const int j = n & 3; return D == 128 ? (2 * j) ^ (j >> 1) : j; };
   const int k_lds_off = stage_row * K_ROW + (stage_piece << 4);
-  const int v_lds_off = stage_row * V_ROW + (((stage_piece >> 1) ^ v_swizzle(stage_row)) << 5) + ((stage_piece & 1) << 4);
+  int v_lds_off[PER_THREAD];
+#pragma unroll
+  for (int i = 0; i < PER_THREAD; ++i)
+    v_lds_off[i] = (stage_row + i * ROW_STEP) * V_ROW + (((stage_piece >> 1) ^ v_swizzle(stage_row + i * ROW_STEP)) << 5) + ((stage_piece & 1) << 4);
 
   // Gathering form: every K/V row is fetched through a table of source rows.  For a temporal
   // head row v of the P-outer order is token row_table[entries + v] (Sec. 4.2; text rows map to
@@ -425,9 +430,16 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
     const int key0 = __builtin_amdgcn_readfirstlane(col_any) * BN;
     const __amdgpu_buffer_rsrc_t rt = __builtin_amdgcn_make_buffer_rsrc(
         const_cast<int32_t*>(a.row_table), 0, 2u * (unsigned)a.nk * BN * 4u, kRsrcFlags);
+    if constexpr (GATHER && PER_THREAD == 4) {
+      const u32x4 e = __builtin_amdgcn_raw_buffer_load_b128(rt, stage_row * 4, tab_base + key0 * 4, 0);
 #pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i)
-      tab[i] = __builtin_amdgcn_raw_buffer_load_b32(rt, (stage_row + i * (THREADS / CPR)) * 4, tab_base + key0 * 4, 0);
+      for (int i = 0; i < 4; ++i) tab[i] = (int)e[i];
+    } else if constexpr (GATHER) {
+      static_assert(!GATHER || PER_THREAD == 4 || PER_THREAD == 2, "one load fetches a thread's row numbers");
+      const u32x2 e = __builtin_amdgcn_raw_buffer_load_b64(rt, stage_row * 4, tab_base + key0 * 4, 0);
+      tab[0] = (int)e[0];
+      tab[1] = (int)e[1];
+    }
   };
 
   auto load_tile = [&](int col_any) {
@@ -452,10 +464,10 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
         const_cast<__bf16*>(vh + (size_t)key0 * D), 0, bytes_left, kRsrcFlags);
 #pragma unroll
     for (int i = 0; i < PER_THREAD; ++i)
-      kst[i] = __builtin_amdgcn_raw_buffer_load_b128(rk, stage_off + i * (THREADS / CPR) * (D * 2), 0, 0);
+      kst[i] = __builtin_amdgcn_raw_buffer_load_b128(rk, stage_off + i * ROW_STEP * (D * 2), 0, 0);
 #pragma unroll
     for (int i = 0; i < PER_THREAD; ++i)
-      vst[i] = __builtin_amdgcn_raw_buffer_load_b128(rv, stage_off + i * (THREADS / CPR) * (D * 2), 0, 0);
+      vst[i] = __builtin_amdgcn_raw_buffer_load_b128(rv, stage_off + i * ROW_STEP * (D * 2), 0, 0);
   };
 
   auto store_tile = [&](int buf, int col) {
@@ -463,10 +475,10 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
     unsigned char* vb = kb + K_BYTES;
 #pragma unroll
     for (int i = 0; i < PER_THREAD; ++i)
-      *reinterpret_cast<u32x4*>(kb + k_lds_off + i * (THREADS / CPR) * K_ROW) = kst[i];
+      *reinterpret_cast<u32x4*>(kb + k_lds_off + i * ROW_STEP * K_ROW) = kst[i];
 #pragma unroll
-    for (int i = 0; i < PER_THREAD; ++i)     // rows a multiple of four apart: the same swizzle
-      *reinterpret_cast<u32x4*>(vb + v_lds_off + i * (THREADS / CPR) * V_ROW) = vst[i];
+    for (int i = 0; i < PER_THREAD; ++i)
+      *reinterpret_cast<u32x4*>(vb + v_lds_off[i]) = vst[i];
     if (MASKABLE && masked && tid < BN) {
       // per-key mask code: the key's frame (spatial) or in-frame position (temporal), or
       // "kept by every query" (text / sink key, unmasked pass), or "out of range"
@@ -596,7 +608,7 @@ __global__ __launch_bounds__(64 * NW, waves_per_simd(D, NW, MODE)) void attn_ker
       // ---- S^T = K Q^T.  Operand reads run PF products ahead of their use (a rolling
       // window of PF operand registers), so after the first few the LDS latency is hidden
       // behind the MFMAs; the scheduling barriers pin the read / product interleave.
-      constexpr int PF = prefetch_depth(D, NW, MASKABLE);
+      constexpr int PF = prefetch_depth(D, NW, MODE);
       constexpr int NS = KB * DS;          // operands of the first product, order (kb, s)
       constexpr int NV = KB * 2 * DB;      // operands of the second product, order (kb, kk, db)
       auto k_operand = [&](int i) -> bf16x8 {
