@@ -72,12 +72,12 @@ constexpr int prefetch_depth(int D, int NW, int MODE) { return D == 128 && NW ==
 constexpr unsigned kRsrcFlags = 0x00020000u;   // raw buffer, 32-bit data format (gfx9 encoding)
 
 // Wavefronts per SIMD the register budget is set for.  Head dimension 128 fills 256 registers
-// (two wavefronts).  At head dimension 64 the accumulators are half as large and the dense and
-// sparse passes fit 168 registers: three workgroups per CU, whose wavefronts cover each other's
-// softmax phases (the longer phase at this head dimension) better than two workgroups with
-// twice the keys per barrier did (4-7 % less time).  The masked forms would spill there.
+// (two wavefronts).  At head dimension 64 the accumulators are half as large and every form fits
+// 168 registers: three workgroups per CU, whose wavefronts cover each other's softmax phases
+// (the longer phase at this head dimension) better than two workgroups with twice the keys per
+// barrier did (4-7 % less time in the dense and sparse passes, 14 % in profiling).
 constexpr int waves_per_simd(int D, int NW, int MODE) {
-  return NW != 4 ? 1 : (D == 64 && (MODE == kDense || MODE == kSparse || MODE == kSparseGather)) ? 3 : 2;
+  return NW != 4 ? 1 : D == 64 ? 3 : 2;
 }
 
 template <int D, int NW, int BN, int MODE, int LW>

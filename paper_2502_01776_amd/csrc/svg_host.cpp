@@ -15,20 +15,20 @@ void note_hip_error(hipError_t e) { g_last_hip_error = e; }
 
 // ---------------------------------------------------------------------------------------------
 // Plan of the profiling passes (see ProfilePlan), from measurements on MI355X with 64 workgroups
-// resident per XCD:
+// resident per XCD (96 at head dimension 64, where three fit a CU):
 //  * Unmasked pass: four parts and two of half their length at the end, so that the workgroups
 //    that finish last are short ones (1-3 % less time than eight equal parts; anything from
 //    four to eight parts measured within 1 % of each other).  Fewer parts for short sequences,
 //    and three when the sampled rows alone already give every XCD hundreds of workgroups.
 //  * Masked passes: one part each, unless the (head, row group) pairs are so few that the two
 //    masked workgroups per pair cannot fill an XCD; then as many parts (up to four) as keep
-//    them within its resident places.  CogVideoX-v1 at 1 % (12 pairs per XCD): two parts,
-//    -25 % time; 0.1 % of the rows at the 119k-token shape (3 pairs): four parts, 3.9 -> 1.3 ms;
+//    them within its resident places.  CogVideoX-v1 at 1 % (12 pairs per XCD): three parts,
+//    -32 % time; 0.1 % of the rows at the 119k-token shape (3 pairs): four parts, 3.9 -> 1.3 ms;
 //    with 15 or more pairs per XCD any cut of the masked passes measured slower (+4-20 %).
 // ---------------------------------------------------------------------------------------------
 namespace {
 
-constexpr int kSlots = 64;            // workgroups resident on one XCD: 32 CUs x 2
+constexpr int kSlots = 64;            // workgroups resident on one XCD: 32 CUs x 2 (x 3 at D = 64)
 
 void fill_bounds(ProfilePlan* p, int n_big, int n_small, int nk) {
   p->n_full = n_big + n_small;
@@ -48,7 +48,8 @@ ProfilePlan profile_plan(const Geo& g, int t) {
   const long long pairs = (long long)g.B * g.H * groups;
   const long long pairs_x = (pairs + 7) / 8;
   ProfilePlan plan = {};
-  plan.n_masked = (int)std::max<long long>(1, std::min<long long>(4, (kSlots - 8) / (2 * pairs_x)));
+  const int slots = g.D == 64 ? kSlots * 3 / 2 : kSlots;
+  plan.n_masked = (int)std::max<long long>(1, std::min<long long>(4, (slots - 8) / (2 * pairs_x)));
   if (g.nk < 24) fill_bounds(&plan, 1, 0, g.nk);
   else if (pairs_x >= 4 * kSlots) fill_bounds(&plan, 1, 2, g.nk);
   else if (g.nk < 96) fill_bounds(&plan, 2, 2, g.nk);
