@@ -221,6 +221,24 @@ def measured_matrix_peak(S, torch, head_dim, ms_target=12.0):
     return out
 
 
+def measured_lds_rates(S, torch, waves=8, iters=4000):
+    """Bytes per clock the LDS of one compute unit delivers for the operand reads and staging
+    writes of the D = 128 attention kernels, with two wavefronts per SIMD as those kernels run
+    (svg_probe_lds: one workgroup, shader clocks per wavefront from the kernel's own clock reads)."""
+    scratch = torch.zeros(16 + 512, dtype=torch.int64, device="cuda")
+    out = {}
+    for form, key in ((0, "k_operand_ds_read_b128"), (1, "vt_operand_ds_read_b64_tr_b16_swizzled_rows"),
+                      (2, "vt_operand_ds_read_b64_tr_b16_plain_rows"), (3, "staging_ds_write_b128")):
+        S.svg_probe_lds(form, waves, 200, scratch)
+        nbytes = S.svg_probe_lds(form, waves, iters, scratch)
+        torch.cuda.synchronize()
+        clocks = float(scratch[:waves].max().item())
+        out[key] = {"bytes_per_clock_per_cu": waves * iters * 16 * nbytes / clocks,
+                    "cu_clocks_per_wave_instruction": clocks / (iters * 16) / waves}
+    out["wavefronts_per_cu"] = waves
+    return out
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -419,6 +437,8 @@ def main():
         out["roofline"]["frac_of_instruction_mix_bound"] = achieved / mix
         out["roofline"]["measured_peak_constant_operands"] = peak_live["products_only_constant_operands"]["tflops"]
         out["roofline"]["measured_peak_detail"] = peak_live
+        # what the LDS of a compute unit delivers for this kernel's operand reads and staging writes (live)
+        out["roofline"]["lds_rates"] = measured_lds_rates(S, torch)
     o8_keep = None
     if not args.no_fp8 and S.svg_fp8_buffer_bytes(sh, S.SVG_FP8_Q) > 0:
         # the same layer with the sparse pass in FP8: profiling as above (bf16), one quantisation pass

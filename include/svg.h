@@ -342,6 +342,24 @@ int svg_sparse_attn_fp8_fwd(const svg_shape_t* shape, const void* q8, const void
 int svg_probe_mfma_bf16(int form, int32_t workgroups, int32_t iterations, const void* operands,
                         float* sink, double* flop_out, void* stream);
 
+/* Measurement aid (no part of the method): what the LDS of one compute unit delivers for the
+ * access patterns of the attention kernels (the roofline discussion needs to know whether the
+ * LDS is a saturated unit).  One workgroup of `waves` wavefronts (1..16; 8 = two per SIMD, as
+ * the D = 128 kernels run) issues `iterations` x 16 LDS instructions of one kind per wavefront:
+ *   form 0   ds_read_b128, the K operand pattern (rows padded by 16 bytes)
+ *   form 1   ds_read_b64_tr_b16, the V^T operand pattern on the swizzled row-major V tile
+ *   form 2   the same read on plain row-major rows (shows what the swizzle is for)
+ *   form 3   ds_write_b128 in the staging pattern
+ *   scratch  device, 16-byte aligned, >= 16 * 8 + 1024 * 4 bytes, written: int64 [16], of which
+ *            entry w receives the shader clocks wavefront w took for its iterations x 16
+ *            instructions (followed by a sink that keeps the reads alive).  The caller reads it
+ *            back after synchronising; bytes per clock of the unit = waves x iterations x 16 x
+ *            (1024 for forms 0 and 3, 512 for forms 1 and 2) / max over w of entry w.
+ * Errors: INVALID_ARG (form, waves, iterations, NULL or misaligned scratch), WORKSPACE (scratch too
+ * small), HIP. */
+int svg_probe_lds(int form, int32_t waves, int32_t iterations, void* scratch, size_t scratch_bytes,
+                  void* stream);
+
 #ifdef __cplusplus
 }
 #endif

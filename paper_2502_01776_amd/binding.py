@@ -32,7 +32,7 @@ EXPORTS = ("svg_strerror", "svg_version", "svg_last_hip_error", "svg_workspace_b
            "svg_sparse_attn_fwd", "svg_sparse_attn_fwd_ex", "svg_dense_attn_fwd",
            "svg_layout_kv_temporal", "svg_sparse_attn_fwd_kv2",
            "svg_fp8_buffer_bytes", "svg_fp8_quantize", "svg_sparse_attn_fp8_fwd", "svg_qk_norm_rope",
-           "svg_probe_mfma_bf16")
+           "svg_probe_mfma_bf16", "svg_probe_lds")
 
 
 class SvgShape(C.Structure):
@@ -107,6 +107,8 @@ def lib():
         L.svg_sparse_attn_fp8_fwd.argtypes = [sp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.svg_probe_mfma_bf16.restype = C.c_int
         L.svg_probe_mfma_bf16.argtypes = [C.c_int, C.c_int32, C.c_int32, vp, vp, C.POINTER(C.c_double), vp]
+        L.svg_probe_lds.restype = C.c_int
+        L.svg_probe_lds.argtypes = [C.c_int, C.c_int32, C.c_int32, vp, C.c_size_t, vp]
         L.svg_dense_attn_fwd.restype = C.c_int
         L.svg_dense_attn_fwd.argtypes = [sp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         _lib = L
@@ -273,3 +275,11 @@ def svg_probe_mfma_bf16(form, workgroups, iterations, operands, sink, stream=Non
     _check(lib().svg_probe_mfma_bf16(int(form), int(workgroups), int(iterations), _ptr(operands), _ptr(sink),
                                      C.byref(flop), _stream(stream)), "svg_probe_mfma_bf16")
     return flop.value
+
+
+def svg_probe_lds(form, waves, iterations, scratch, stream=None) -> int:
+    """Enqueues the LDS rate probe; returns the bytes one wave instruction of this form moves.  Entry w of
+    scratch (viewed as int64) receives the shader clocks wavefront w took."""
+    _check(lib().svg_probe_lds(int(form), int(waves), int(iterations), _ptr(scratch),
+                               scratch.numel() * scratch.element_size(), _stream(stream)), "svg_probe_lds")
+    return 1024 if form in (0, 3) else 512

@@ -92,9 +92,88 @@ __global__ __launch_bounds__(kProbeThreads, FORM == 2 ? 3 : 2) void probe_kernel
   sink[blockIdx.x * kProbeThreads + tid] = s;
 }
 
+// What the LDS of one compute unit delivers for the access patterns of the attention kernels at
+// head dimension 128: one workgroup of `waves` wavefronts issues `iters` x 16 LDS instructions of
+// one kind per wavefront (the loaded values are consumed by empty statements, so nothing but the LDS
+// instructions and their waits is timed) and every wavefront writes the shader clocks that took to
+// ticks[wave].
+//   form 0  ds_read_b128 of a K operand (rows padded by 16 bytes, 32 rows x 16 bytes per half wave)
+//   form 1  ds_read_b64_tr_b16 of a V^T operand from row-major rows whose 32-byte slots are
+//           XOR-swizzled with the row's two low bits (the layout the kernels stage V in)
+//   form 2  the same read from plain row-major rows
+//   form 3  ds_write_b128 in the staging pattern (16 lanes write one row)
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) i16x4 lds_i16x4;
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+constexpr int kLdsProbeInstructions = 16;
+
+template <int FORM>
+__global__ __launch_bounds__(1024) void lds_probe_kernel(long long* ticks, int* sink, int iters) {
+  constexpr int D = 128, V_ROW = D * 2, K_ROW = D * 2 + 16;
+  __shared__ __attribute__((aligned(16))) unsigned char lds[64 * K_ROW];
+  const int tid = threadIdx.x, lane = tid & 63;
+  for (int i = tid; i < 64 * K_ROW / 4; i += blockDim.x) reinterpret_cast<unsigned*>(lds)[i] = i * 2654435761u;
+  __syncthreads();
+  const int g = lane >> 5, r = lane & 31;
+  const int s = lane & 15, j = s >> 2, h = (lane >> 4) & 1;
+  const int swizzle = FORM == 1 ? (2 * j) ^ (j >> 1) : 0;
+  int v_off[4];
+#pragma unroll
+  for (int db = 0; db < 4; ++db) v_off[db] = (4 * g + j) * V_ROW + (((2 * db + h) ^ swizzle) << 5) + ((s & 3) << 3);
+  const int k_off = r * K_ROW + (g << 4);
+  const i32x4 payload = {tid, lane, g, r};
+  __syncthreads();
+  const long long t0 = clock64();
+  for (int it = 0; it < iters; ++it) {
+    // the array's address goes into the statement so that it counts as read and written there:
+    // loads are not hoisted out of the loop and the stores of an iteration are not dropped
+    asm volatile("" ::"v"(lds) : "memory");
+    // all instructions of an iteration are issued before the first result is waited for
+    i32x4 wide[FORM == 0 ? kLdsProbeInstructions : 1];
+    i16x4 narrow[FORM == 1 || FORM == 2 ? kLdsProbeInstructions : 1];
+#pragma unroll
+    for (int u = 0; u < kLdsProbeInstructions; ++u) {
+      if (FORM == 0) {        // operands (kb, s) of the first product: 2 key blocks x 8 channel steps
+        wide[u] = *reinterpret_cast<const i32x4*>(lds + k_off + ((u & 1) * 32) * K_ROW + (u >> 1) * 32);
+      } else if (FORM == 1 || FORM == 2) {   // operands (step, half, db) of the second product
+        narrow[u] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+            (lds_i16x4*)(lds + v_off[u & 3] + ((u >> 2) & 1) * 8 * V_ROW + (u >> 3) * 16 * V_ROW));
+      } else {                // 16 lanes write one row; 4 rows per instruction, 64 rows in all
+        *reinterpret_cast<i32x4*>(lds + ((lane >> 4) + 4 * u) * K_ROW + ((lane & 15) << 4)) = payload;
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < kLdsProbeInstructions; ++u) {
+      if (FORM == 0) asm volatile("" ::"v"(wide[u]));
+      if (FORM == 1 || FORM == 2) asm volatile("" ::"v"(narrow[u]));
+    }
+  }
+  asm volatile("" ::"v"(lds) : "memory");
+  const long long t1 = clock64();
+  if (lane == 0) ticks[tid >> 6] = t1 - t0;
+  sink[tid] = reinterpret_cast<const int*>(lds)[tid];
+}
+
 }  // namespace
 
 }  // namespace svg
+
+extern "C" int svg_probe_lds(int form, int32_t waves, int32_t iterations, void* scratch, size_t scratch_bytes,
+                             void* stream) {
+  if (form < 0 || form > 3 || waves <= 0 || waves > 16 || iterations <= 0 || !scratch) return SVG_ERR_INVALID_ARG;
+  if (svg::misaligned16(scratch)) return SVG_ERR_INVALID_ARG;
+  if (scratch_bytes < 16 * sizeof(long long) + 1024 * sizeof(int)) return SVG_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  long long* ticks = static_cast<long long*>(scratch);
+  int* sink = reinterpret_cast<int*>(ticks + 16);
+  (void)hipGetLastError();
+  const dim3 grid(1), block(64 * waves);
+  if (form == 0) hipLaunchKernelGGL((svg::lds_probe_kernel<0>), grid, block, 0, s, ticks, sink, iterations);
+  else if (form == 1) hipLaunchKernelGGL((svg::lds_probe_kernel<1>), grid, block, 0, s, ticks, sink, iterations);
+  else if (form == 2) hipLaunchKernelGGL((svg::lds_probe_kernel<2>), grid, block, 0, s, ticks, sink, iterations);
+  else hipLaunchKernelGGL((svg::lds_probe_kernel<3>), grid, block, 0, s, ticks, sink, iterations);
+  return svg::hip_status(hipGetLastError());
+}
 
 extern "C" int svg_probe_mfma_bf16(int form, int32_t workgroups, int32_t iterations, const void* operands,
                                    float* sink, double* flop_out, void* stream) {

@@ -317,6 +317,14 @@ def test_rate_probe_argument_checks_without_gpu():
     assert lib.svg_probe_mfma_bf16(0, 8, 0, a, a, C.byref(flop), None) == -1
     assert lib.svg_probe_mfma_bf16(0, 8, 1, None, a, C.byref(flop), None) == -1
     assert lib.svg_probe_mfma_bf16(1, 8, 1, a + 2, a, C.byref(flop), None) == -1
+    need = 16 * 8 + 1024 * 4
+    assert lib.svg_probe_lds(4, 8, 1, a, need, None) == -1                           # unknown form
+    assert lib.svg_probe_lds(0, 0, 1, a, need, None) == -1
+    assert lib.svg_probe_lds(0, 17, 1, a, need, None) == -1                          # a workgroup holds 16 wavefronts
+    assert lib.svg_probe_lds(0, 8, 0, a, need, None) == -1
+    assert lib.svg_probe_lds(0, 8, 1, None, need, None) == -1
+    assert lib.svg_probe_lds(0, 8, 1, a + 8, need, None) == -1
+    assert lib.svg_probe_lds(0, 8, 1, a, need - 1, None) == -3                       # scratch too small
 
 
 def test_qk_norm_rope_argument_checks_without_gpu():

@@ -50,3 +50,24 @@ def test_matrix_core_rate_probe_runs_and_counts_its_work():
         torch.cuda.synchronize()
         assert flop == 64 * 4 * 10 * 16 * 2.0 * 32 * 32 * 16
         assert torch.isfinite(sink).all()
+
+
+@pytest.mark.gpu
+def test_lds_rate_probe_shows_what_the_swizzle_is_for():
+    """The LDS probe times the operand reads of the attention kernels on one compute unit: with two
+    wavefronts per SIMD the transposing read of the swizzled V tile must be conflict-free (a few clocks
+    per wave instruction) and clearly faster than the same read on plain row-major rows."""
+    import torch
+    import paper_2502_01776_amd as S
+    scratch = torch.zeros(16 + 512, dtype=torch.int64, device="cuda")
+    clocks = {}
+    for form in (0, 1, 2, 3):
+        S.svg_probe_lds(form, 8, 200, scratch)          # warm-up
+        S.svg_probe_lds(form, 8, 2000, scratch)
+        torch.cuda.synchronize()
+        t = scratch[:8].cpu().numpy()
+        assert (t > 0).all()
+        clocks[form] = float(t.max()) / (2000 * 16) / 8          # CU clocks per wave instruction
+    assert clocks[1] < 4.5 and clocks[2] > 1.8 * clocks[1], clocks
+    assert clocks[0] < 8.0 and clocks[3] > clocks[0], clocks
+
