@@ -37,6 +37,10 @@ def test_json_line_has_the_contract_fields():
     # measured ceilings of the same box, live: zeros > random operands > with the kernel's instruction mix > the kernel
     assert rf["measured_peak_constant_operands"] > rf["measured_peak"] > rf["measured_peak_with_kernel_instruction_mix"] > rf["achieved"]
     assert cb["host_cpus"] >= 1 and cb["cores"] >= 1 and rf["traffic_live"] in (False, None)
+    # the LDS of a compute unit, live: conflict-free reads far above the staging writes, the swizzle worth > 2x
+    lr = rf["lds_rates"]
+    assert lr["k_operand_ds_read_b128"]["bytes_per_clock_per_cu"] > 150 > lr["staging_ds_write_b128"]["bytes_per_clock_per_cu"]
+    assert lr["vt_operand_ds_read_b64_tr_b16_swizzled_rows"]["bytes_per_clock_per_cu"] > 2 * lr["vt_operand_ds_read_b64_tr_b16_plain_rows"]["bytes_per_clock_per_cu"]
 
 
 @pytest.mark.gpu
