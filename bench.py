@@ -59,6 +59,8 @@ def parse():
     ap.add_argument("--no-qk-norm-rope", action="store_true",
                     help="skip the timing of the fused QK-norm + rotary embedding pass on q and k (Table 2), "
                          "otherwise reported in the 'qk_norm_rope' object beside a plain PyTorch version")
+    ap.add_argument("--no-hip-graph", action="store_true",
+                    help="skip the timing of the same layer captured once as a HIP graph and replayed")
     ap.add_argument("--no-measured-peak", action="store_true",
                     help="skip the two product loops that measure what the matrix cores sustain on this box")
     ap.add_argument("--only", default="", help="time a single stage only (profile|layout|sparse|dense); "
@@ -350,6 +352,28 @@ def main():
     wall_ms = (time.perf_counter() - t0) * 1e3 / args.steps
     breakdown = {name: float(np.median([a.elapsed_time(b) for a, b in lst])) for name, lst in marks.items()}
 
+    # The same layer captured once as a HIP graph and replayed (no entry point allocates, synchronises
+    # or records a memset): what a caller gains who removes the launch gaps of the layer's six kernels.
+    graph_ms = None
+    if not args.no_hip_graph:
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        graph.replay()
+        torch.cuda.synchronize()
+        t1 = time.perf_counter()
+        for _ in range(args.steps):
+            graph.replay()
+        torch.cuda.synchronize()
+        graph_ms = (time.perf_counter() - t1) * 1e3 / args.steps
+        del graph
+
     labels_np = labels.cpu().numpy()
     n_temporal = int(labels_np.sum())
     nnz = [int(rp[-1]) for rp, _ in lists_np]
@@ -406,6 +430,8 @@ def main():
                    "N": N, "D": D, "w_s": cfg["w_s"], "w_t": cfg["w_t"], "tile": [cfg["block_m"], cfg["block_n"]],
                    "profiled_rows": t, "temporal_heads": n_temporal, "kept_tile_fraction": kept_fraction},
         "ms_per_layer": wall_ms,
+        "hip_graph": None if graph_ms is None else {"ms_per_layer_replayed": graph_ms, "ms_per_layer_eager": wall_ms,
+                                                    "what": "the layer's launches captured once and replayed"},
         "breakdown_ms": breakdown,
         "dense_ms": dense_ms,
         "dense_tflops": None if dense_ms is None else dense_flops / (dense_ms * 1e-3) / 1e12,
