@@ -70,8 +70,11 @@ constexpr int kPrioFirstProduct = 2;
 constexpr int kPrioSecondProduct = 1;
 constexpr int kCohort = 64;   // dense: consecutive query tiles that share an XCD (and its L2) at a time
 // LDS operand reads kept in flight ahead of the products: eight where the registers allow it
-// (the dense and the plain sparse pass at head dimension 128; 0.3 % over four), four elsewhere
-constexpr int prefetch_depth(int D, int NW, int MODE) { return D == 128 && NW == 4 && (MODE == kDense || MODE == kSparse) ? 8 : 4; }
+// (the dense and the plain sparse pass at head dimension 128; 0.3 % over four), six in the
+// gathering form (0.5-0.9 % over four), four elsewhere
+constexpr int prefetch_depth(int D, int NW, int MODE) {
+  return D != 128 || NW != 4 ? 4 : MODE == kDense || MODE == kSparse ? 8 : MODE == kSparseGather ? 6 : 4;
+}
 constexpr unsigned kRsrcFlags = 0x00020000u;   // raw buffer, 32-bit data format (gfx9 encoding)
 
 // Wavefronts per SIMD the register budget is set for.  Head dimension 128 fills 256 registers
