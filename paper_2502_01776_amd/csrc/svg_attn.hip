@@ -64,8 +64,8 @@ constexpr int kNoTile = 0x7fffffff;
 // Wave priority while a wavefront issues a batch of products (0 elsewhere).  The two
 // wavefronts sharing a SIMD then settle into opposite phases: the products of one run
 // back to back while the other's softmax and staging instructions fill the gaps.  The first
-// product of a tile ranks above the second (1 % less time than equal ranks; the other way
-// round 1 % more): a wavefront that starts a tile is not held up by one that finishes one.
+// product of a tile ranks above the second (1 % less time than equal ranks, 1 % more with the
+// ranks swapped): a wavefront that starts a tile is not held up by one that finishes one.
 constexpr int kPrioFirstProduct = 2;
 constexpr int kPrioSecondProduct = 1;
 constexpr int kCohort = 64;   // dense: consecutive query tiles that share an XCD (and its L2) at a time
